@@ -1,0 +1,111 @@
+"""ORACLE -- test infrastructure only: chunk construction and chunk scheduling in plain Python.
+
+Follows the paper's Algorithm 1 (section 4.1) and Algorithm 2 (section 4.2) step by step.  Where the
+paper leaves a choice open the reading is stated at the step that takes it.
+
+A chunk is a dict:
+    tokens      number of tokens in the chunk (<= chunk_size)
+    prefix_len  tokens of the same long sequence that lie in earlier chunks (0 for packed chunks)
+    group       id of its dependency group; idx_in_group its 0-based position there
+    segments    list of (seq_id, seq_start, length): which tokens of which input sequence
+A group is a dict: seq_id (the long sequence, or -1 for a packed chunk) and chunks (ids, ascending
+dependency order = forward order).
+"""
+
+
+def _try_pack(order, lens, n_bins, cap):
+    """One bin-packing attempt (Algorithm 1, the 'try binpacking into BinCnt bins' step).
+
+    The paper names no heuristic.  Reading: sequences, longest first, each go to the bin with
+    the smallest load (ties: lowest bin number), which keeps the chunks about equally full as
+    section 1 asks; the attempt fails as soon as a sequence does not fit there.
+    """
+    load = [0] * n_bins
+    members = [[] for _ in range(n_bins)]
+    for i in order:
+        b = min(range(n_bins), key=lambda x: (load[x], x))
+        if load[b] + lens[i] > cap:          # limit is inclusive: a bin may be exactly full
+            return None
+        load[b] += lens[i]
+        members[b].append(i)
+    return members
+
+
+def build_chunks(seq_lens, chunk_size):
+    """Algorithm 1.  Returns (chunks, groups)."""
+    lens = [int(x) for x in seq_lens]
+    cap = int(chunk_size)
+    if cap < 1 or any(x < 1 for x in lens):
+        raise ValueError("chunk_size and every length must be >= 1")
+
+    # 'longer than ChunkSize' are split; a sequence of exactly ChunkSize tokens is one full
+    # standalone chunk (the paper's example: a 2-Unit sequence with ChunkSize 2 Units).
+    long_ids = [i for i, x in enumerate(lens) if x > cap]
+    short_ids = [i for i, x in enumerate(lens) if x <= cap]
+
+    chunks, groups = [], []
+    for i in long_ids:                       # input order
+        gid = len(groups)
+        groups.append({"seq_id": i, "chunks": []})
+        start, m = 0, 0
+        while start < lens[i]:
+            n = min(cap, lens[i] - start)
+            groups[gid]["chunks"].append(len(chunks))
+            chunks.append({"tokens": n, "prefix_len": start, "group": gid, "idx_in_group": m,
+                           "segments": [(i, start, n)]})
+            start += n
+            m += 1
+
+    if short_ids:
+        order = sorted(short_ids, key=lambda i: (-lens[i], i))
+        bins = None
+        for n_bins in range(1, len(short_ids) + 1):     # first bin count that works wins
+            bins = _try_pack(order, lens, n_bins, cap)
+            if bins is not None:
+                break
+        for members in bins:
+            if not members:
+                continue
+            gid = len(groups)
+            groups.append({"seq_id": -1, "chunks": [len(chunks)]})
+            segs = [(i, 0, lens[i]) for i in sorted(members)]   # input order inside a chunk
+            chunks.append({"tokens": sum(s[2] for s in segs), "prefix_len": 0, "group": gid,
+                           "idx_in_group": 0, "segments": segs})
+    return chunks, groups
+
+
+FWD_KEEP, FWD_DISCARD, BWD = 0, 1, 2
+
+
+def schedule_group(chunk_ids, K):
+    """Algorithm 2 for one dependency group: list of (op, chunk_id).
+
+    Readings of the printed listing, both forced by section 4.2's prose: the chunks whose
+    activations are kept are the LAST K (the first N-K run forward twice), and the final loop
+    visits the first N-K chunks in DESCENDING order (a chunk's key/value gradient needs every
+    later chunk's contribution first).
+    """
+    if K < 1:
+        raise ValueError("K must be >= 1")
+    n = len(chunk_ids)
+    ops = []
+    if n <= K:
+        ops += [(FWD_KEEP, c) for c in chunk_ids]
+        ops += [(BWD, c) for c in reversed(chunk_ids)]
+        return ops
+    for m, c in enumerate(chunk_ids):
+        ops.append((FWD_KEEP if m >= n - K else FWD_DISCARD, c))
+    for c in reversed(chunk_ids[n - K:]):
+        ops.append((BWD, c))
+    for c in reversed(chunk_ids[:n - K]):
+        ops.append((FWD_KEEP, c))
+        ops.append((BWD, c))
+    return ops
+
+
+def build_schedule(groups, K):
+    """Algorithm 2 applied to every group in group order; each group's ops are contiguous."""
+    ops = []
+    for g in groups:
+        ops += schedule_group(list(g["chunks"]), K)
+    return ops

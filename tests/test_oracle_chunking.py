@@ -1,0 +1,138 @@
+"""Pins for the chunk-construction and scheduling oracle (CPU only).
+
+The paper fixes: the chunk counts of its worked example (tests/golden/paper_examples.txt), that long
+sequences are cut into ChunkSize slices and short ones bin-packed into as few bins as the packing
+attempt manages (Algorithm 1), the forward/backward order inside a dependency group and the number
+of repeated forward passes (section 4.2).  The particular packing heuristic is the oracle's own
+reading; it is checked here for validity and against exhaustive search, not against the paper.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+from oracle import chunking as CK
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_examples.txt")
+
+
+def golden_cases():
+    out = []
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        c, lens, n = [x.strip() for x in line.split(";")]
+        out.append((int(c), [int(x) for x in lens.split()], int(n)))
+    return out
+
+
+@pytest.mark.parametrize("C,lens,n_chunks", golden_cases())
+def test_paper_worked_example(C, lens, n_chunks):
+    chunks, groups = CK.build_chunks(lens, C)
+    assert len(chunks) == n_chunks
+
+
+def test_paper_example_structure():
+    # ChunkSize 2: the 4-Unit sequence gives two dependent slices; the 2-Unit sequence is one full
+    # standalone chunk; the two 1-Unit sequences share one exactly-full chunk.
+    chunks, groups = CK.build_chunks([1, 1, 2, 4], 2)
+    assert [c["segments"] for c in chunks] == [[(3, 0, 2)], [(3, 2, 2)], [(2, 0, 2)], [(0, 0, 1), (1, 0, 1)]]
+    assert [c["prefix_len"] for c in chunks] == [0, 2, 0, 0]
+    assert [g["seq_id"] for g in groups] == [3, -1, -1] and groups[0]["chunks"] == [0, 1]
+    chunks, _ = CK.build_chunks([1, 1, 2, 4], 4)
+    assert [c["segments"] for c in chunks] == [[(3, 0, 4)], [(0, 0, 1), (1, 0, 1), (2, 0, 2)]]
+
+
+def check_valid(lens, C, chunks, groups):
+    seen = {i: np.zeros(L, int) for i, L in enumerate(lens)}
+    for cid, c in enumerate(chunks):
+        assert 1 <= c["tokens"] <= C and c["tokens"] == sum(s[2] for s in c["segments"])
+        for (sid, st, n) in c["segments"]:
+            seen[sid][st:st + n] += 1
+        g = groups[c["group"]]
+        assert g["chunks"][c["idx_in_group"]] == cid
+        if g["seq_id"] >= 0:                       # dependent slice
+            assert len(c["segments"]) == 1 and lens[g["seq_id"]] > C
+            sid, st, n = c["segments"][0]
+            assert sid == g["seq_id"] and st == c["prefix_len"] == c["idx_in_group"] * C
+            last = c["idx_in_group"] == len(g["chunks"]) - 1
+            assert n == C or (last and n == lens[sid] - st)
+        else:
+            assert c["prefix_len"] == 0 and len(g["chunks"]) == 1
+            assert all(st == 0 and n == lens[sid] and n <= C for (sid, st, n) in c["segments"])
+            assert [s[0] for s in c["segments"]] == sorted(s[0] for s in c["segments"])
+    assert all((v == 1).all() for v in seen.values())       # every token exactly once
+
+
+def optimal_bins(items, C):
+    """Exhaustive minimum number of bins (tiny inputs only)."""
+    n = len(items)
+    for b in range(1, n + 1):
+        for assign in itertools.product(range(b), repeat=n):
+            load = [0] * b
+            for x, a in zip(items, assign):
+                load[a] += x
+            if max(load) <= C:
+                return b
+    return n
+
+
+def test_random_lists_are_valid_and_near_optimal():
+    rng = np.random.default_rng(0)
+    for trial in range(300):
+        n = int(rng.integers(0, 9))
+        C = int(rng.integers(1, 40))
+        lens = [int(x) for x in rng.integers(1, 3 * C + 2, size=n)]
+        chunks, groups = CK.build_chunks(lens, C)
+        check_valid(lens, C, chunks, groups)
+        short = [x for x in lens if x <= C]
+        packed = sum(1 for g in groups if g["seq_id"] < 0)
+        assert packed >= -(-sum(short) // C)
+        if len(short) <= 7:
+            assert packed >= optimal_bins(short, C)           # optimum is a lower bound
+            assert packed <= optimal_bins(short, C) + 2       # and the heuristic stays close
+        n_long = sum(-(-x // C) for x in lens if x > C)
+        assert len(chunks) == n_long + packed
+
+
+def test_bad_arguments():
+    for lens, C in (([3, 0], 4), ([3], 0), ([-1], 4)):
+        with pytest.raises(ValueError):
+            CK.build_chunks(lens, C)
+    assert CK.build_chunks([], 8) == ([], [])
+
+
+@pytest.mark.parametrize("N,K", [(1, 1), (4, 1), (4, 2), (4, 4), (3, 7), (7, 3)])
+def test_schedule_counts_and_order(N, K):
+    ids = list(range(10, 10 + N))
+    ops = CK.schedule_group(ids, K)
+    n_fwd = sum(1 for op, _ in ops if op != CK.BWD)
+    n_bwd = sum(1 for op, _ in ops if op == CK.BWD)
+    # section 4.2: the first N-K chunks run forward twice when N > K
+    assert n_fwd == (N + (N - K) if N > K else N) and n_bwd == N
+    live, first_fwd_done, bwd_done = set(), set(), set()
+    for op, c in ops:
+        m = c - 10
+        if op in (CK.FWD_KEEP, CK.FWD_DISCARD):
+            assert all(x in first_fwd_done for x in range(m))        # ascending forward dependency
+            first_fwd_done.add(m)
+            if op == CK.FWD_KEEP:
+                live.add(m)
+                assert len(live) <= K                                 # at most K chunks' activations
+        else:
+            assert m in live                                          # backward needs kept activations
+            assert all(x in bwd_done for x in range(m + 1, N))        # descending backward dependency
+            live.discard(m)
+            bwd_done.add(m)
+    assert bwd_done == set(range(N)) and not live
+
+
+def test_schedule_whole_plan_groups_contiguous():
+    chunks, groups = CK.build_chunks([9, 2, 30, 3], 8)
+    ops = CK.build_schedule(groups, 1)
+    seen_groups = [chunks[c]["group"] for _, c in ops]
+    assert seen_groups == sorted(seen_groups)
+    with pytest.raises(ValueError):
+        CK.build_schedule(groups, 0)
