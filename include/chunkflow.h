@@ -1,0 +1,187 @@
+/*
+ * chunkflow.h -- C ABI of the ChunkFlow hot path on one MI355X (gfx950).
+ *
+ * The library does two things:
+ *   1. host side: turn a batch of sequence lengths into uniformly sized chunks (paper section 4.1,
+ *      Algorithm 1) and order the chunks' forward/backward passes (section 4.2, Algorithm 2);
+ *   2. device side: causal attention forward and backward over one chunk, where a chunk is either
+ *      several short sequences packed under a per-sequence causal mask (section 2.2) or one slice
+ *      of a long sequence that also attends to the retained key/value state of that sequence's
+ *      earlier chunks, the key/value gradients of those earlier rows being accumulated by the
+ *      later chunks' backward passes (section 4.2).
+ *
+ * Conventions
+ *   - Every function returns CF_OK (0) or a negative error code; nothing throws, aborts or prints.
+ *     cf_last_error() gives a message for the last failing call on the calling thread.
+ *   - "host" / "device" on a pointer says where the memory must live.  The library never takes
+ *     ownership of a caller's buffer and never allocates device memory.
+ *   - Device entry points only enqueue work on the given HIP stream: no synchronisation.
+ *   - Tensors are token-major: X[token][head][d] with d contiguous; strides are in ELEMENTS.
+ */
+#ifndef CHUNKFLOW_H
+#define CHUNKFLOW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CF_OK = 0,
+    CF_EINVAL = -1,       /* NULL pointer, size out of range, inconsistent arguments          */
+    CF_EUNSUPPORTED = -2, /* well-formed but not built (head_dim, dtype)                        */
+    CF_ENOMEM = -3,       /* host allocation failed                                             */
+    CF_EHIP = -4          /* a HIP call failed; cf_last_error() carries hipGetErrorString text  */
+};
+
+/* Message of the last error on this thread; static storage, valid until the next failing call. */
+const char *cf_last_error(void);
+/* major*10000 + minor*100 + patch */
+int cf_version(void);
+
+/* ============================================================================================
+ * Host planner (no HIP calls).
+ * ========================================================================================== */
+
+typedef struct cf_plan cf_plan; /* opaque; owned by the caller after a successful build */
+
+/*
+ * Chunk construction, Algorithm 1 (section 4.1).
+ *   seq_lens   host, [n_seqs], every entry >= 1
+ *   chunk_size 1 .. INT32_MAX
+ * Sequences LONGER than chunk_size are cut into ceil(len/chunk_size) consecutive slices, one chunk
+ * each, forming one dependency group in ascending order.  The others (length <= chunk_size) are
+ * bin-packed: for BinCnt = 1, 2, ... the sequences, longest first (ties: input order), each go
+ * to the currently least-loaded bin (ties: lowest bin); the first BinCnt for which no bin exceeds
+ * chunk_size wins.  Each non-empty bin becomes one packed chunk (a group of size 1) whose
+ * segments are in input order.  Chunk ids: slices of long sequences first (input order), then
+ * packed chunks (bin order).
+ * Errors: NULL seq_lens with n_seqs > 0, NULL out, n_seqs < 0, chunk_size out of range, a length
+ * < 1 -> CF_EINVAL and *out is untouched.  n_seqs == 0 gives a valid empty plan.
+ */
+int cf_build_chunks(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size, cf_plan **out);
+void cf_plan_free(cf_plan *plan); /* NULL is fine */
+
+/* Read-only view of a plan.  All pointers are host memory borrowed from the plan and stay valid
+ * until cf_plan_free.  Segments of chunk c are [chunk_seg_ptr[c], chunk_seg_ptr[c+1]). */
+typedef struct {
+    int64_t n_chunks, n_segments, n_groups, total_tokens, chunk_size;
+    const int64_t *chunk_seg_ptr;      /* [n_chunks+1]                                          */
+    const int32_t *chunk_tokens;       /* [n_chunks]  tokens in the chunk (<= chunk_size)        */
+    const int64_t *chunk_prefix_len;   /* [n_chunks]  tokens of the same sequence in earlier chunks */
+    const int32_t *chunk_group;        /* [n_chunks]                                            */
+    const int32_t *chunk_idx_in_group; /* [n_chunks]  0-based                                   */
+    const int64_t *seg_seq_id;         /* [n_segments] index into seq_lens                      */
+    const int64_t *seg_seq_start;      /* [n_segments] first token of that sequence covered     */
+    const int32_t *seg_len;            /* [n_segments]                                          */
+    const int32_t *cu_seqlens;         /* [n_segments+n_chunks]; chunk c's local exclusive prefix
+                                          sums (n_seg_c+1 entries, first is 0) start at index
+                                          chunk_seg_ptr[c] + c                                   */
+    const int64_t *group_chunk_ptr;    /* [n_groups+1]                                          */
+    const int64_t *group_chunks;       /* [n_chunks]  chunk ids per group, ascending dependency (forward) order */
+    const int64_t *group_seq_id;       /* [n_groups]  the long sequence, or -1 for a packed chunk */
+} cf_plan_view;
+int cf_plan_get(const cf_plan *plan, cf_plan_view *out);
+
+/*
+ * State-aware chunk scheduling, Algorithm 2 (section 4.2), applied to every group in group order.
+ * K >= 1 is the number of chunks whose activations may be kept.  For a group of N chunks:
+ *   N <= K : FWD_KEEP 0..N-1, then BWD N-1..0.
+ *   N >  K : FWD_DISCARD 0..N-K-1, FWD_KEEP N-K..N-1, BWD N-1..N-K, then for m = N-K-1 .. 0:
+ *            FWD_KEEP m, BWD m   (the first N-K chunks run forward twice).
+ * *ops is host memory owned by the plan, valid until the next cf_build_schedule on this plan or
+ * cf_plan_free.
+ */
+enum { CF_OP_FWD_KEEP = 0, CF_OP_FWD_DISCARD = 1, CF_OP_BWD = 2 };
+typedef struct {
+    int32_t op;
+    int32_t reserved;
+    int64_t chunk;
+} cf_sched_op;
+int cf_build_schedule(cf_plan *plan, int32_t K, const cf_sched_op **ops, int64_t *n_ops);
+
+/* ============================================================================================
+ * Device kernels.
+ * ========================================================================================== */
+
+enum { CF_BF16 = 0, CF_FP32 = 1 };
+/* flags: CF_FLAG_SCALAR_KERNELS runs the plain scalar kernels even where an MFMA kernel exists
+ * (same results up to rounding; for cross-checks). */
+enum { CF_FLAG_SCALAR_KERNELS = 1 };
+
+/*
+ * One chunk of attention (sections 2.1, 2.2, 4.2).  The chunk has n_segments segments; segment g
+ * owns query rows [cu_seqlens_q[g], cu_seqlens_q[g+1]) of q/o and key rows
+ * [cu_seqlens_k[g], cu_seqlens_k[g+1]) of k/v, with Lk_g >= Lq_g >= 1.  The causal mask is aligned
+ * to the END of the keys: query i (local) sees key j (local) iff j <= i + (Lk_g - Lq_g).
+ *   packed chunk    : cu_seqlens_k == cu_seqlens_q, k/v are the chunk's own keys/values.
+ *   dependent chunk : one segment, cu_seqlens_k = {0, P+T}; k/v point at the base of the
+ *                     sequence's state buffer whose rows [0,P) were written by earlier chunks and
+ *                     whose rows [P,P+T) the caller filled with this chunk's keys/values.
+ * Query head h reads key/value head h / (n_q_heads / n_kv_heads).
+ * dtype CF_BF16: q,k,v,o are bf16, arithmetic accumulates in fp32.  CF_FP32: all fp32.
+ * cu_seqlens are NOT validated (they live on the device): the caller guarantees they are
+ * non-decreasing, start at 0, end at n_tokens (q) / n_kv_tokens (k) and satisfy Lk_g >= Lq_g.
+ */
+typedef struct {
+    int32_t dtype;                      /* CF_BF16 or CF_FP32                                    */
+    int32_t flags;                      /* 0, or CF_FLAG_* bits                                  */
+    int32_t n_q_heads, n_kv_heads;      /* n_q_heads % n_kv_heads == 0                           */
+    int32_t head_dim;                   /* 64 or 128                                             */
+    float softmax_scale;
+    int32_t n_tokens;                   /* query rows T >= 1                                     */
+    int32_t n_kv_tokens;                /* key rows  (sum of Lk_g) >= n_tokens                   */
+    int32_t n_segments;                 /* >= 1                                                  */
+    const int32_t *cu_seqlens_q;        /* device, [n_segments+1]                                */
+    const int32_t *cu_seqlens_k;        /* device, [n_segments+1]                                */
+    const void *q;                      /* device, [T][Hq][D]                                    */
+    int64_t q_stride_tok, q_stride_head;
+    const void *k, *v;                  /* device, [n_kv_tokens][Hkv][D], same strides for both  */
+    int64_t kv_stride_tok, kv_stride_head;
+    void *o;                            /* device, [T][Hq][D], written                           */
+    int64_t o_stride_tok, o_stride_head;
+    float *lse;                         /* device, [Hq][T] natural-log sum of exponentials, written */
+} cf_attn_fwd_params;
+
+/* Enqueue the forward pass.  Errors: NULL pointers, sizes < 1, n_kv_tokens < n_tokens,
+ * Hq % Hkv != 0, misaligned base pointers or strides (bf16: multiples of 8 elements, fp32: of 4)
+ * -> CF_EINVAL; head_dim / dtype not built -> CF_EUNSUPPORTED; launch failure -> CF_EHIP. */
+int cf_attn_fwd(const cf_attn_fwd_params *p, void *hip_stream);
+
+/*
+ * Backward pass of the same chunk.  f repeats the forward call's arguments (o and lse are inputs
+ * here).  d_q is overwritten.  d_k / d_v are fp32 [n_kv_tokens][Hkv][D] and are ADDED TO: for a
+ * dependent chunk they point at the base of the sequence's gradient state, so that rows [0,P)
+ * collect the contributions of later chunks when the group's chunks run in descending order; the
+ * caller zeroes them once per long sequence / per packed chunk.  Launches on one stream are
+ * ordered, and inside one launch every d_k/d_v element has a single writer.
+ * workspace: device scratch of at least cf_attn_bwd_workspace_bytes(&f) bytes, 256-byte aligned;
+ * contents need not be initialised and are not preserved.
+ */
+typedef struct {
+    cf_attn_fwd_params f;
+    const void *d_o;                    /* device, [T][Hq][D], dtype as f.dtype                  */
+    int64_t do_stride_tok, do_stride_head;
+    void *d_q;                          /* device, [T][Hq][D], dtype as f.dtype, overwritten     */
+    int64_t dq_stride_tok, dq_stride_head;
+    float *d_k, *d_v;                   /* device, fp32, accumulated                             */
+    int64_t dkv_stride_tok, dkv_stride_head;
+    void *workspace;
+    int64_t workspace_bytes;
+} cf_attn_bwd_params;
+
+/* Bytes of workspace cf_attn_bwd needs for these shapes (only sizes/dtype are read), or a
+ * negative error code. */
+int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p);
+int cf_attn_bwd(const cf_attn_bwd_params *p, void *hip_stream);
+
+/* Number of unmasked (query, key) pairs of a chunk described by HOST copies of its cu_seqlens:
+ * sum over segments of Lq*(Lk-Lq) + Lq*(Lq+1)/2.  Used to turn run time into FLOP/s. */
+int64_t cf_count_pairs(const int32_t *cu_seqlens_q_host, const int32_t *cu_seqlens_k_host,
+                       int32_t n_segments);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHUNKFLOW_H */

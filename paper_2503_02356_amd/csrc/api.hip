@@ -1,0 +1,115 @@
+// C ABI of the device entry points: argument checks, workspace carving, kernel selection.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_fwd(const cf_attn_fwd_params *p, const char *who, bool sizes_only)
+{
+    if (!p) return cf::fail(CF_EINVAL, "%s: params is NULL", who);
+    if (p->dtype != CF_BF16 && p->dtype != CF_FP32)
+        return cf::fail(CF_EUNSUPPORTED, "%s: dtype %d not supported", who, p->dtype);
+    if (p->head_dim != 64 && p->head_dim != 128)
+        return cf::fail(CF_EUNSUPPORTED, "%s: head_dim %d not supported (64 or 128)", who, p->head_dim);
+    if (p->n_q_heads < 1 || p->n_kv_heads < 1 || p->n_q_heads % p->n_kv_heads != 0)
+        return cf::fail(CF_EINVAL, "%s: n_q_heads %d must be a positive multiple of n_kv_heads %d", who,
+                        p->n_q_heads, p->n_kv_heads);
+    if (p->n_q_heads > 65535) return cf::fail(CF_EINVAL, "%s: n_q_heads %d > 65535", who, p->n_q_heads);
+    if (p->n_tokens < 1 || p->n_segments < 1 || p->n_kv_tokens < p->n_tokens)
+        return cf::fail(CF_EINVAL, "%s: need n_tokens >= 1, n_segments >= 1, n_kv_tokens >= n_tokens (got %d, %d, %d)",
+                        who, p->n_tokens, p->n_segments, p->n_kv_tokens);
+    if (p->n_segments > p->n_tokens)
+        return cf::fail(CF_EINVAL, "%s: n_segments %d > n_tokens %d (empty segments are not allowed)", who,
+                        p->n_segments, p->n_tokens);
+    if (sizes_only) return CF_OK;
+    if (p->flags & ~CF_FLAG_SCALAR_KERNELS) return cf::fail(CF_EINVAL, "%s: unknown flags 0x%x", who, p->flags);
+    if (!p->cu_seqlens_q || !p->cu_seqlens_k || !p->q || !p->k || !p->v || !p->o || !p->lse)
+        return cf::fail(CF_EINVAL, "%s: NULL device pointer", who);
+    if (!(p->softmax_scale == p->softmax_scale))
+        return cf::fail(CF_EINVAL, "%s: softmax_scale is NaN", who);
+    const int64_t vec = p->dtype == CF_BF16 ? 8 : 4;  // elements per 16-byte access
+    const int64_t D = p->head_dim;
+    const int64_t strides[] = {p->q_stride_tok, p->q_stride_head, p->kv_stride_tok, p->kv_stride_head,
+                               p->o_stride_tok, p->o_stride_head};
+    for (int64_t s : strides)
+        if (s < D || s % vec != 0)
+            return cf::fail(CF_EINVAL, "%s: stride %lld must be >= head_dim and a multiple of %lld elements", who,
+                            (long long)s, (long long)vec);
+    if (!aligned(p->q, 16) || !aligned(p->k, 16) || !aligned(p->v, 16) || !aligned(p->o, 16) ||
+        !aligned(p->lse, 4) || !aligned(p->cu_seqlens_q, 4) || !aligned(p->cu_seqlens_k, 4))
+        return cf::fail(CF_EINVAL, "%s: q, k, v, o must be 16-byte aligned", who);
+    return CF_OK;
+}
+
+bool use_mfma(const cf_attn_fwd_params &p)
+{
+    return p.dtype == CF_BF16 && p.head_dim == 128 && !(p.flags & CF_FLAG_SCALAR_KERNELS);
+}
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+int64_t delta_bytes(const cf_attn_fwd_params &p) { return round_up((int64_t)p.n_q_heads * p.n_tokens * 4, 256); }
+int64_t dq_acc_bytes(const cf_attn_fwd_params &p)
+{
+    return use_mfma(p) ? round_up((int64_t)p.n_tokens * p.n_q_heads * p.head_dim * 4, 256) : 0;
+}
+
+int hip_fail(const char *who, hipError_t e)
+{
+    return cf::fail(CF_EHIP, "%s: %s", who, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" int cf_attn_fwd(const cf_attn_fwd_params *p, void *hip_stream)
+{
+    if (int rc = check_fwd(p, "cf_attn_fwd", false)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = use_mfma(*p) ? cf::launch_mfma_fwd(*p, s) : cf::launch_simple_fwd(*p, s);
+    return e == hipSuccess ? CF_OK : hip_fail("cf_attn_fwd", e);
+}
+
+extern "C" int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p)
+{
+    if (int rc = check_fwd(p, "cf_attn_bwd_workspace_bytes", true)) return rc;
+    if (p->flags & ~CF_FLAG_SCALAR_KERNELS)
+        return cf::fail(CF_EINVAL, "cf_attn_bwd_workspace_bytes: unknown flags 0x%x", p->flags);
+    return delta_bytes(*p) + dq_acc_bytes(*p);
+}
+
+extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
+{
+    const char *who = "cf_attn_bwd";
+    if (!b) return cf::fail(CF_EINVAL, "%s: params is NULL", who);
+    if (int rc = check_fwd(&b->f, who, false)) return rc;
+    const cf_attn_fwd_params &p = b->f;
+    if (!b->d_o || !b->d_q || !b->d_k || !b->d_v || !b->workspace)
+        return cf::fail(CF_EINVAL, "%s: NULL device pointer", who);
+    const int64_t vec = p.dtype == CF_BF16 ? 8 : 4, D = p.head_dim;
+    const int64_t strides[] = {b->do_stride_tok, b->do_stride_head, b->dq_stride_tok, b->dq_stride_head};
+    for (int64_t s : strides)
+        if (s < D || s % vec != 0)
+            return cf::fail(CF_EINVAL, "%s: stride %lld must be >= head_dim and a multiple of %lld elements", who,
+                            (long long)s, (long long)vec);
+    if (b->dkv_stride_tok < D || b->dkv_stride_head < D || b->dkv_stride_tok % 4 || b->dkv_stride_head % 4)
+        return cf::fail(CF_EINVAL, "%s: d_k/d_v strides must be >= head_dim and multiples of 4 elements", who);
+    if (!aligned(b->d_o, 16) || !aligned(b->d_q, 16) || !aligned(b->d_k, 16) || !aligned(b->d_v, 16) ||
+        !aligned(b->workspace, 256))
+        return cf::fail(CF_EINVAL, "%s: d_o, d_q, d_k, d_v must be 16-byte and workspace 256-byte aligned", who);
+    const int64_t need = delta_bytes(p) + dq_acc_bytes(p);
+    if (b->workspace_bytes < need)
+        return cf::fail(CF_EINVAL, "%s: workspace has %lld bytes, %lld needed", who, (long long)b->workspace_bytes,
+                        (long long)need);
+    cf::BwdWorkspace ws;
+    ws.delta = static_cast<float *>(b->workspace);
+    ws.dq_acc = use_mfma(p) ? reinterpret_cast<float *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = cf::launch_delta(*b, ws, s);
+    if (e != hipSuccess) return hip_fail(who, e);
+    e = use_mfma(p) ? cf::launch_mfma_bwd(*b, ws, s) : cf::launch_simple_bwd(*b, ws, s);
+    return e == hipSuccess ? CF_OK : hip_fail(who, e);
+}

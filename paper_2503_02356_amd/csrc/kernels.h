@@ -1,0 +1,28 @@
+// Internal launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "chunkflow.h"
+
+namespace cf {
+
+// Backward scratch layout inside the caller's workspace (all fp32):
+//   delta   [Hq][T]         rowsum(dO * O)
+//   dq_acc  [T][Hq][D]      bf16 MFMA path only: fp32 accumulation target of dQ
+struct BwdWorkspace {
+    float *delta;
+    float *dq_acc;
+};
+
+// Plain scalar kernels: any supported head_dim, fp32 or bf16 storage, fp32 arithmetic.
+hipError_t launch_simple_fwd(const cf_attn_fwd_params &p, hipStream_t s);
+hipError_t launch_simple_bwd(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
+
+// delta[h][t] = sum_d dO[t][h][d] * O[t][h][d]; optionally zero-fills dq_acc on the way.
+hipError_t launch_delta(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
+
+// bf16 MFMA kernels, head_dim 128.
+hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s);
+hipError_t launch_mfma_bwd(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
+
+}  // namespace cf

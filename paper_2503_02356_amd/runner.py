@@ -1,0 +1,150 @@
+"""Executes a chunk plan on one GPU: the StateStore and the launch order of paper section 4.2.
+
+Memory placement only -- every arithmetic step runs inside cf_attn_fwd / cf_attn_bwd.
+Per long sequence one key/value state buffer [L,Hkv,D] and one fp32 gradient state of the same
+shape stay resident; a dependent chunk's call passes their base pointers with n_kv_tokens = P+T,
+so the prefix and the chunk's own rows are one contiguous range.  Packed chunks own their K/V.
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class ChunkAttention:
+    def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0):
+        self.plan, self.Hq, self.Hkv, self.D = plan, n_q_heads, n_kv_heads, head_dim
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(head_dim))
+        self.dev, self.flags = torch.device(device), flags
+        self.chunks = []          # per chunk: dict of device tensors and params
+        self.state = {}           # group id -> dict(k, v, dk, dv) for long sequences
+
+    # ------------------------------------------------------------------ data placement
+    def load(self, values):
+        """values(seq_id, L) -> dict(q,k,v,d_o) of fp32 numpy arrays [L,H,D] (already representable
+        in the compute dtype)."""
+        p, dev, dt = self.plan, self.dev, self.tdtype
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt)
+        cache = {}
+
+        def get(sid, L):
+            if sid not in cache:
+                cache.clear()     # segments of one sequence are consecutive in the plan; keep one
+                cache[sid] = values(sid, L)
+            return cache[sid]
+        seq_len = {}
+        for s in range(p.n_segments):
+            sid = int(p.seg_seq_id[s])
+            seq_len[sid] = max(seq_len.get(sid, 0), int(p.seg_seq_start[s]) + int(p.seg_len[s]))
+        ws_bytes = 0
+        for c in range(p.n_chunks):
+            segs = p.chunk_segments(c)
+            T, P = int(p.chunk_tokens[c]), int(p.chunk_prefix_len[c])
+            g = int(p.chunk_group[c])
+            dependent = int(p.group_seq_id[g]) >= 0
+            ch = {"T": T, "P": P, "dependent": dependent, "segs": segs, "group": g}
+            ch["q"] = torch.empty((T, self.Hq, self.D), dtype=dt, device=dev)
+            ch["d_o"] = torch.empty_like(ch["q"])
+            ch["o"] = torch.empty_like(ch["q"])
+            ch["d_q"] = torch.empty_like(ch["q"])
+            ch["lse"] = torch.empty((self.Hq, T), dtype=torch.float32, device=dev)
+            cu = p.chunk_cu_seqlens(c)
+            ch["cu_q_host"] = cu.copy()
+            ch["cu_q"] = torch.from_numpy(cu.copy()).to(dev)
+            if dependent:
+                sid, start, n = segs[0]
+                L = seq_len[sid]
+                vals = get(sid, L)
+                if g not in self.state:
+                    self.state[g] = {"k": up(vals["k"]), "v": up(vals["v"]),
+                                     "dk": torch.zeros((L, self.Hkv, self.D), dtype=torch.float32, device=dev),
+                                     "dv": torch.zeros((L, self.Hkv, self.D), dtype=torch.float32, device=dev)}
+                st = self.state[g]
+                ch["k"], ch["v"] = st["k"][:P + T], st["v"][:P + T]
+                ch["dk"], ch["dv"] = st["dk"][:P + T], st["dv"][:P + T]
+                ch["q"].copy_(up(vals["q"][start:start + n]))
+                ch["d_o"].copy_(up(vals["d_o"][start:start + n]))
+                ch["cu_k_host"] = np.array([0, P + T], dtype=np.int32)
+            else:
+                ch["k"] = torch.empty((T, self.Hkv, self.D), dtype=dt, device=dev)
+                ch["v"] = torch.empty_like(ch["k"])
+                ch["dk"] = torch.zeros((T, self.Hkv, self.D), dtype=torch.float32, device=dev)
+                ch["dv"] = torch.zeros_like(ch["dk"])
+                for i, (sid, start, n) in enumerate(segs):
+                    vals = get(sid, n)
+                    a, b = int(cu[i]), int(cu[i + 1])
+                    ch["q"][a:b].copy_(up(vals["q"]))
+                    ch["d_o"][a:b].copy_(up(vals["d_o"]))
+                    ch["k"][a:b].copy_(up(vals["k"]))
+                    ch["v"][a:b].copy_(up(vals["v"]))
+                ch["cu_k_host"] = cu.copy()
+            ch["cu_k"] = torch.from_numpy(ch["cu_k_host"].copy()).to(dev)
+            ch["pairs"] = B.cf_count_pairs(ch["cu_q_host"], ch["cu_k_host"])
+            ch["fwd"] = B.make_fwd_params(ch["q"], ch["k"], ch["v"], ch["o"], ch["lse"], ch["cu_q"], ch["cu_k"],
+                                          self.scale, self.flags)
+            ws_bytes = max(ws_bytes, B.cf_attn_bwd_workspace_bytes(ch["fwd"]))
+            self.chunks.append(ch)
+        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        for ch in self.chunks:
+            ch["bwd"] = B.make_bwd_params(ch["fwd"], ch["d_o"], ch["d_q"], ch["dk"], ch["dv"], self.workspace)
+        self.total_pairs = sum(ch["pairs"] for ch in self.chunks)
+        return self
+
+    # ------------------------------------------------------------------ launches
+    def zero_grads(self):
+        for st in self.state.values():
+            st["dk"].zero_(); st["dv"].zero_()
+        for ch in self.chunks:
+            if not ch["dependent"]:
+                ch["dk"].zero_(); ch["dv"].zero_()
+
+    def forward_order(self):
+        return [c for g in range(self.plan.n_groups) for c in self.plan.group(g)]
+
+    def backward_order(self):
+        return [c for g in range(self.plan.n_groups) for c in reversed(self.plan.group(g))]
+
+    def run_forward(self, stream=None):
+        for c in self.forward_order():          # ascending inside each group
+            B.cf_attn_fwd(self.chunks[c]["fwd"], stream)
+
+    def run_backward(self, stream=None):
+        for c in self.backward_order():         # descending inside each group
+            B.cf_attn_bwd(self.chunks[c]["bwd"], stream)
+
+    def run_schedule(self, K, stream=None):
+        """Algorithm 2 with K kept chunks: chunks marked FWD_DISCARD run forward (their K/V state is
+        what later chunks need) and run forward again right before their backward."""
+        for op, c in self.plan.schedule(K):
+            if op == B.CF_OP_BWD:
+                B.cf_attn_bwd(self.chunks[c]["bwd"], stream)
+            else:
+                B.cf_attn_fwd(self.chunks[c]["fwd"], stream)
+
+    # ------------------------------------------------------------------ results
+    def results(self):
+        """Per input sequence: o, lse, dq, dk, dv as fp64 numpy arrays (re-indexed through the plan)."""
+        torch.cuda.synchronize()
+        out = {}
+        f64 = lambda t: t.detach().to(torch.float64).cpu().numpy()
+        for ch in self.chunks:
+            o, lse, dq = f64(ch["o"]), f64(ch["lse"]), f64(ch["d_q"])
+            dk = dv = None
+            if not ch["dependent"]:
+                dk, dv = f64(ch["dk"]), f64(ch["dv"])
+            cu = ch["cu_q_host"]
+            for i, (sid, start, n) in enumerate(ch["segs"]):
+                a, b = int(cu[i]), int(cu[i + 1])
+                r = out.setdefault(sid, {})
+                if ch["dependent"]:
+                    st = self.state[ch["group"]]
+                    L = st["k"].shape[0]
+                    if "o" not in r:
+                        r.update(o=np.zeros((L, self.Hq, self.D)), lse=np.zeros((self.Hq, L)),
+                                 dq=np.zeros((L, self.Hq, self.D)), dk=f64(st["dk"]), dv=f64(st["dv"]))
+                    r["o"][start:start + n], r["dq"][start:start + n] = o[a:b], dq[a:b]
+                    r["lse"][:, start:start + n] = lse[:, a:b]
+                else:
+                    r.update(o=o[a:b], lse=lse[:, a:b], dq=dq[a:b], dk=dk[a:b], dv=dv[a:b])
+        return out

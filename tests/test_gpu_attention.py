@@ -1,0 +1,130 @@
+"""GPU parity: the library's chunked attention against the fp64 oracle's UNSPLIT attention, element by
+element, re-indexed through the plan.  Tolerances are the north-star's (tests/parity.py)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as OA
+from paper_2503_02356_amd import binding as B
+from paper_2503_02356_amd import inputs
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+SCALAR = B.CF_FLAG_SCALAR_KERNELS
+
+
+def test_config1_tiny_fp32_full():
+    lens, C = inputs.seq_lens("tiny_fp32", 0, P.oracle_count_chunks)
+    lens = [int(x) for x in lens]
+    got, eng = P.run_gpu(lens, C, 1, 1, 64, "fp32", seed=1)
+    assert [ch["P"] for ch in eng.chunks[:3]] == [0, 256, 512]
+    ref = P.run_oracle(lens, 1, 1, 64, "fp32", seed=1)
+    errs = P.check(got, ref, "fp32", "config 1")
+    print("config1", errs)
+
+
+@pytest.mark.parametrize("dtype,D,flags", [("fp32", 128, 0), ("bf16", 64, 0), ("bf16", 128, SCALAR), ("bf16", 128, 0)])
+def test_small_mixed_plan(dtype, D, flags):
+    """Long sequence split in 4 (non-dividing tail) + packed short ones, GQA 6/2, ragged lengths."""
+    lens = [700, 33, 1, 120, 64, 65, 17, 128, 5, 250]
+    C = 200
+    got, _ = P.run_gpu(lens, C, 6, 2, D, dtype, seed=2, flags=flags)
+    ref = P.run_oracle(lens, 6, 2, D, dtype, seed=2)
+    print(dtype, D, flags, P.check(got, ref, dtype, f"{dtype} D={D} flags={flags}"))
+
+
+@pytest.mark.parametrize("cfg,sd,Hq,Hkv", [("packed_8k", 16, 28, 4), ("long32k_mixed", 16, 28, 4),
+                                           ("longtail_16k", 64, 32, 8), ("long256k_32k", 64, 16, 2)])
+def test_scaled_down_configs_bf16(cfg, sd, Hq, Hkv):
+    """Structurally identical small instances of configs 2-5 (chunk size and lengths divided by sd)."""
+    lens, C = inputs.seq_lens(cfg, 0, P.oracle_count_chunks, scale_down=sd)
+    lens = [int(x) for x in lens]
+    if cfg == "longtail_16k":
+        lens = lens[:120] + [max(lens)]          # keep the oracle's work to seconds; keep one long sequence
+    got, eng = P.run_gpu(lens, C, Hq, Hkv, 128, "bf16", seed=3)
+    ref = P.run_oracle(lens, Hq, Hkv, 128, "bf16", seed=3)
+    print(cfg, "chunks", len(eng.chunks), P.check(got, ref, "bf16", cfg))
+
+
+@pytest.mark.parametrize("flags", [SCALAR, 0])
+def test_edge_cases(flags):
+    cases = [
+        ([1], 8),                          # one token
+        ([1, 1, 1, 1, 1, 1, 1, 1], 8),     # eight one-token documents in one chunk
+        ([129], 128),                      # tail slice of one token with a 128-token prefix
+        ([127, 128, 129, 2], 128),         # around a tile edge
+        ([513], 64),                       # nine slices, last has one token
+        ([64] * 9, 192),
+    ]
+    for lens, C in cases:
+        got, _ = P.run_gpu(lens, C, 4, 2, 128, "bf16", seed=4, flags=flags)
+        ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=4)
+        P.check(got, ref, "bf16", f"lens={lens} C={C}")
+
+
+def test_recompute_schedule_gives_same_result():
+    """Algorithm 2 with K=1: the first N-1 chunks run forward twice; results must not change."""
+    lens = [900, 40, 300]
+    a, _ = P.run_gpu(lens, 256, 4, 2, 128, "bf16", seed=5)
+    b, _ = P.run_gpu(lens, 256, 4, 2, 128, "bf16", seed=5, K=1)
+    ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=5)
+    P.check(b, ref, "bf16", "K=1")
+    for sid in a:
+        for n in ("o", "lse", "dk", "dv"):
+            assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
+
+
+def test_strided_views_and_nonzero_initial_grads():
+    """q/k/v as views into one packed buffer; dK/dV must be added to, dQ overwritten."""
+    torch.manual_seed(0)
+    dev = "cuda:0"
+    T, Hq, Hkv, D = 300, 4, 2, 128
+    qkv = torch.randn(T, Hq + 2 * Hkv, D, device=dev).to(torch.bfloat16)
+    q, k, v = qkv[:, :Hq], qkv[:, Hq:Hq + Hkv], qkv[:, Hq + Hkv:]
+    d_o = torch.randn(T, Hq, D, device=dev).to(torch.bfloat16)
+    cu_host = np.array([0, 100, 101, 300], dtype=np.int32)
+    cu = torch.from_numpy(cu_host).to(dev)
+    o = torch.empty(T, Hq, D, device=dev, dtype=torch.bfloat16)
+    lse = torch.empty(Hq, T, device=dev, dtype=torch.float32)
+    scale = 1 / np.sqrt(D)
+    fp = B.make_fwd_params(q, k, v, o, lse, cu, cu, scale)
+    B.cf_attn_fwd(fp)
+    dq = torch.full((T, Hq, D), 7.0, device=dev, dtype=torch.bfloat16)
+    dkv0 = torch.randn(2, T, Hkv, D, device=dev)
+    dkv = dkv0.clone()
+    ws = torch.empty(B.cf_attn_bwd_workspace_bytes(fp), dtype=torch.uint8, device=dev)
+    B.cf_attn_bwd(B.make_bwd_params(fp, d_o, dq, dkv[0], dkv[1], ws))
+    torch.cuda.synchronize()
+    f = lambda t: t.double().cpu().numpy()
+    ro, rlse = OA.chunk_attn_fwd(f(q), f(k), f(v), cu_host, cu_host, np.float32(scale))
+    rdk, rdv = np.zeros((T, Hkv, D)), np.zeros((T, Hkv, D))
+    rdq = OA.chunk_attn_bwd(f(q), f(k), f(v), ro, rlse, f(d_o), cu_host, cu_host, np.float32(scale), rdk, rdv)
+    got = {0: dict(o=f(o), lse=f(lse), dq=f(dq), dk=f(dkv[0] - dkv0[0]), dv=f(dkv[1] - dkv0[1]))}
+    P.check(got, {0: dict(o=ro, lse=rlse, dq=rdq, dk=rdk, dv=rdv)}, "bf16", "strided")
+
+
+def test_forward_and_dkv_are_deterministic():
+    lens = [1500, 200, 77]
+    a, _ = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=6)
+    b, _ = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=6)
+    for sid in a:
+        for n in ("o", "lse", "dk", "dv"):
+            assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
+
+
+def test_device_entry_point_errors():
+    dev = "cuda:0"
+    q = torch.zeros(16, 2, 128, device=dev, dtype=torch.bfloat16)
+    cu = torch.tensor([0, 16], device=dev, dtype=torch.int32)
+    lse = torch.zeros(2, 16, device=dev)
+    fp = B.make_fwd_params(q, q, q, q.clone(), lse, cu, cu, 0.1)
+    ws = torch.empty(8, dtype=torch.uint8, device=dev)          # too small
+    bp = B.make_bwd_params(fp, q, q.clone(), torch.zeros(16, 2, 128, device=dev), torch.zeros(16, 2, 128, device=dev), ws)
+    with pytest.raises(B.CfError) as e:
+        B.cf_attn_bwd(bp)
+    assert e.value.code == B.CF_EINVAL and "workspace" in str(e.value)
+    fp.q += 2                                                    # misaligned
+    with pytest.raises(B.CfError):
+        B.cf_attn_fwd(fp)

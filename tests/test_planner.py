@@ -1,0 +1,118 @@
+"""Host planner of the library against the Python oracle: descriptors must be bit-exact (CPU only)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import chunking as CK
+from paper_2503_02356_amd import binding as B
+from paper_2503_02356_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def assert_same_plan(lens, C):
+    chunks, groups = CK.build_chunks(lens, C)
+    p = B.cf_build_chunks(lens, C)
+    assert p.n_chunks == len(chunks) and p.n_groups == len(groups)
+    assert p.total_tokens == int(np.sum(lens)) and p.chunk_size == C
+    assert p.n_segments == sum(len(c["segments"]) for c in chunks)
+    for c, ch in enumerate(chunks):
+        assert p.chunk_segments(c) == [tuple(s) for s in ch["segments"]]
+        assert int(p.chunk_tokens[c]) == ch["tokens"] and int(p.chunk_prefix_len[c]) == ch["prefix_len"]
+        assert int(p.chunk_group[c]) == ch["group"] and int(p.chunk_idx_in_group[c]) == ch["idx_in_group"]
+        cu = np.concatenate([[0], np.cumsum([s[2] for s in ch["segments"]])])
+        assert np.array_equal(p.chunk_cu_seqlens(c), cu)
+    for g, gr in enumerate(groups):
+        assert p.group(g) == gr["chunks"] and int(p.group_seq_id[g]) == gr["seq_id"]
+    for K in (1, 2, 5):
+        assert p.schedule(K) == CK.build_schedule(groups, K)
+    p.close()
+    return len(chunks)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
+    declared = set(re.findall(r"\b(cf_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    so = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(so, name), name
+    assert B.cf_version() >= 100
+
+
+def test_paper_examples():
+    assert assert_same_plan([1, 1, 2, 4], 2) == 4
+    assert assert_same_plan([1, 1, 2, 4], 4) == 2
+
+
+def test_random_lists_bit_exact():
+    rng = np.random.default_rng(11)
+    for trial in range(1500):
+        n = int(rng.integers(0, 40))
+        C = int(rng.integers(1, 200))
+        kind = trial % 3
+        if kind == 0:
+            lens = rng.integers(1, 3 * C + 2, size=n)
+        elif kind == 1:
+            lens = np.clip(np.rint(rng.lognormal(np.log(max(C / 8, 1)), 0.9, size=n)), 1, 5 * C).astype(np.int64)
+        else:
+            lens = rng.choice([1, C, C + 1, max(1, C // 2), 2 * C], size=n)     # boundary lengths, many ties
+        assert_same_plan([int(x) for x in lens], C)
+
+
+@pytest.mark.parametrize("cfg,sd", [("tiny_fp32", 1), ("packed_8k", 1), ("long32k_mixed", 1),
+                                    ("longtail_16k", 8), ("long256k_32k", 1)])
+def test_workload_shapes(cfg, sd):
+    count = lambda lens, C: len(CK.build_chunks(lens, C)[0])
+    lens, C = inputs.seq_lens(cfg, 0, count, scale_down=sd)
+    n = assert_same_plan([int(x) for x in lens], C)
+    if cfg == "packed_8k":
+        assert n == 16
+    if cfg == "long32k_mixed":
+        assert n == 12
+    if cfg == "long256k_32k":
+        assert n == 12
+
+
+def test_errors():
+    L = B.lib()
+    out = ctypes.c_void_p(1234)
+    one = np.array([3, 0], dtype=np.int64)
+    ptr = one.ctypes.data_as(ctypes.c_void_p)
+    assert L.cf_build_chunks(ptr, 2, 4, ctypes.byref(out)) == B.CF_EINVAL and out.value == 1234
+    assert b"seq_lens[1]" in L.cf_last_error()
+    assert L.cf_build_chunks(ptr, 1, 0, ctypes.byref(out)) == B.CF_EINVAL
+    assert L.cf_build_chunks(ptr, 1, 2 ** 31, ctypes.byref(out)) == B.CF_EINVAL
+    assert L.cf_build_chunks(ptr, -1, 4, ctypes.byref(out)) == B.CF_EINVAL
+    assert L.cf_build_chunks(None, 1, 4, ctypes.byref(out)) == B.CF_EINVAL
+    assert L.cf_build_chunks(ptr, 1, 4, None) == B.CF_EINVAL
+    assert out.value == 1234
+    L.cf_plan_free(None)
+    p = B.cf_build_chunks([], 8)
+    assert p.n_chunks == 0 and p.n_groups == 0 and p.schedule(1) == []
+    with pytest.raises(B.CfError):
+        B.cf_build_chunks([5, 9], 4).schedule(0)
+    assert B.cf_count_pairs([0, 3, 5], [0, 3, 5]) == 6 + 3
+    assert B.cf_count_pairs([0, 4], [0, 10]) == 4 * 6 + 10
+
+
+def test_device_entry_points_reject_bad_arguments_without_a_gpu():
+    """Argument checks happen on the host before any HIP call."""
+    p = B.AttnFwdParams()
+    assert B.lib().cf_attn_fwd(None, None) == B.CF_EINVAL
+    p.dtype, p.head_dim, p.n_q_heads, p.n_kv_heads = B.CF_BF16, 96, 4, 2
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EUNSUPPORTED
+    p.head_dim, p.n_q_heads = 128, 5
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL
+    p.n_q_heads, p.n_tokens, p.n_kv_tokens, p.n_segments = 4, 16, 8, 1
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL          # fewer keys than queries
+    p.n_kv_tokens = 16
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL          # NULL pointers
+    assert b"NULL" in B.lib().cf_last_error()
+    assert B.cf_attn_bwd_workspace_bytes(p) >= 4 * 16 * 4 + 16 * 4 * 128 * 4
+    b = B.AttnBwdParams()
+    assert B.lib().cf_attn_bwd(None, None) == B.CF_EINVAL
+    assert B.lib().cf_attn_bwd(ctypes.byref(b), None) < 0
