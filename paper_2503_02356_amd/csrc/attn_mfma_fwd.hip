@@ -1,4 +1,220 @@
+// bf16 MFMA forward kernel for one chunk, head_dim 128 (paper sections 2.1, 2.2, 4.2: causal mask per
+// packed sequence; a dependent chunk's queries also read the retained key/value prefix).
+//
+// One workgroup = 4 wavefronts = 128 consecutive query rows of one segment and one query head; each
+// wavefront owns 32 rows.  Key/value tiles of 64 rows are staged through LDS (double buffered) and
+// shared by the four wavefronts.  Everything is computed TRANSPOSED so that a lane owns one query:
+//     S^T = K Q^T   (A = K tile rows from LDS, B = Q^T kept in registers for the whole kernel)
+//     O^T += V^T P^T (A = V^T through transposing LDS reads, B = P^T straight from the S^T registers)
+// With the query on the lane axis the row maximum and row sum are in-lane reductions plus one exchange
+// between lane l and lane l^32, the running rescale is one scalar per lane, and P never leaves registers.
+// Only tiles that intersect the causal diagonal apply a mask; tiles above it are never visited.
+#include <hip/hip_runtime.h>
+
 #include "kernels.h"
+#include "mfma_common.h"
+
 namespace cf {
-hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s) { return launch_simple_fwd(p, s); }
+namespace {
+
+constexpr int BM = 128;        // query rows per workgroup
+constexpr int BN = 64;         // key rows per tile
+constexpr int D = 128;
+constexpr int K_STRIDE = 272;  // bytes per key row in LDS: 256 + 16 so that 16 rows hit distinct 16-byte bank groups
+constexpr int V_STRIDE = 320;  // bytes per value row: 256 + 64 so that 4 rows x 64 bytes are conflict free
+constexpr int K_BYTES = BN * K_STRIDE, V_BYTES = BN * V_STRIDE;
+constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
+
+struct TileLoad {
+    i32x4 k[4], v[4];
+};
+
+// Each of the 256 threads fetches 4 x 16 bytes of the K tile and of the V tile (row = idx/16, 16-byte column = idx%16).
+__device__ __forceinline__ void load_tile(TileLoad &r, const char *kbase, const char *vbase, int64_t row_bytes,
+                                          int tile_start, int last_row)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int idx = threadIdx.x + 256 * c;
+        const int row = min(tile_start + (idx >> 4), last_row);  // rows past the segment repeat its last row (masked later)
+        const int64_t off = (int64_t)row * row_bytes + (idx & 15) * 16;
+        r.k[c] = *(const i32x4 *)(kbase + off);
+        r.v[c] = *(const i32x4 *)(vbase + off);
+    }
 }
+
+__device__ __forceinline__ void store_tile(const TileLoad &r, char *stage)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int idx = threadIdx.x + 256 * c;
+        *(i32x4 *)(stage + (idx >> 4) * K_STRIDE + (idx & 15) * 16) = r.k[c];
+        *(i32x4 *)(stage + K_BYTES + (idx >> 4) * V_STRIDE + (idx & 15) * 16) = r.v[c];
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
+{
+    __shared__ __attribute__((aligned(16))) char smem[2 * STAGE_BYTES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int half = lane >> 5, col = lane & 31;
+
+    // Block id -> (tile rank, head).  The key/value head varies fastest so that the workgroups an XCD
+    // receives (ids are dealt round-robin over the 8 XCDs) keep re-reading the same K/V head in its L2.
+    const int G = p.n_q_heads / p.n_kv_heads;
+    int id = blockIdx.x;
+    const int kh = id % p.n_kv_heads;
+    id /= p.n_kv_heads;
+    const int h = kh * G + id % G;
+    const int rank = id / G;
+
+    int seg, tile_in_seg;
+    if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) return;
+    const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
+    const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
+    const int off = lk - lq;                         // prefix keys every row of the segment sees
+    const int q_tile0 = tile_in_seg * BM;
+    const int rows_valid = min(BM, lq - q_tile0);
+    const int kmax = q_tile0 + rows_valid + off;     // keys [0, kmax) are visible to some row of the tile
+    const int n_tiles = (kmax + BN - 1) / BN;
+
+    const int wq0 = q_tile0 + wave * 32;             // first row of this wavefront (segment-local)
+    const int wave_kmax = min(kmax, wq0 + 32 + off); // keys this wavefront needs (<= 0 rows valid: nothing)
+    const bool wave_active = wq0 < lq;
+    const int iq = wq0 + col;                        // this lane's query row
+    const int amax = iq + off;                       // last visible key of this lane's row
+
+    const int64_t kv_row_bytes = p.kv_stride_tok * 2;
+    const char *kbase = (const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
+    const char *vbase = (const char *)p.v + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
+
+    // Q^T fragments: lane (col, half) holds row iq, d = 16*ks + 8*half + 0..7.
+    bf16x8 qf[8];
+    {
+        const int row = q_seg0 + min(iq, lq - 1);
+        const char *qrow = (const char *)p.q + ((int64_t)row * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 32 + half * 16);
+    }
+
+    f32x16 o_acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) o_acc[i][j] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;            // running max (log2 units) and this lane's partial row sum
+    const float c2 = p.softmax_scale * 1.44269504088896340736f;
+
+    TileLoad regs;
+    load_tile(regs, kbase, vbase, kv_row_bytes, 0, lk - 1);
+    store_tile(regs, smem);
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int tile_start = t * BN;
+        char *stage = smem + (t & 1) * STAGE_BYTES;
+        const bool more = t + 1 < n_tiles;
+        if (more) load_tile(regs, kbase, vbase, kv_row_bytes, tile_start + BN, lk - 1);
+
+        if (wave_active && tile_start < wave_kmax) {
+            // ---- S^T = K Q^T : two 32-key blocks
+            f32x16 s[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
+                const char *krow = stage + (mb * 32 + col) * K_STRIDE + half * 16;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) s[mb] = mfma32(lds_read_b128(krow + ks * 32), qf[ks], s[mb]);
+            }
+            // ---- causal mask, only on tiles that cross this wavefront's diagonal
+            if (tile_start + BN - 1 > wq0 + off) {
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = tile_start + mb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
+                        if (key > amax) s[mb][i] = -INFINITY;
+                    }
+            }
+            // ---- online softmax (log2 domain)
+            float mx = s[0][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m_run, mx * c2);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // first tile: exp2(-inf) = 0
+            m_run = m_new;
+            float rs = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    s[mb][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][i], c2, -m_new));
+                    rs += s[mb][i];
+                }
+            l_run = l_run * alpha + rs;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) o_acc[db][j] *= alpha;
+            }
+            // ---- O^T += V^T P^T : contraction over the 64 keys in 4 groups of 16
+            const char *vst = stage + K_BYTES;
+            const int r16 = lane & 15;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int tq = 0; tq < 2; ++tq) {
+                    const bf16x8 pb = pack8(s[mb][8 * tq + 0], s[mb][8 * tq + 1], s[mb][8 * tq + 2], s[mb][8 * tq + 3],
+                                            s[mb][8 * tq + 4], s[mb][8 * tq + 5], s[mb][8 * tq + 6], s[mb][8 * tq + 7]);
+                    // register 8*tq + j of block mb is key mb*32 + 16*tq + (j/4)*8 + 4*half + j%4
+                    const int k0 = mb * 32 + 16 * tq + half * 4;
+                    const char *va = vst + (k0 + (r16 >> 2)) * V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (r16 & 3)) * 2;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        const bf16x8 a = lds_read_tr_pair(va + db * 64, va + db * 64 + 8 * V_STRIDE);
+                        o_acc[db] = mfma32(a, pb, o_acc[db]);
+                    }
+                }
+        }
+        if (more) store_tile(regs, smem + ((t + 1) & 1) * STAGE_BYTES);
+        __syncthreads();
+    }
+
+    if (!wave_active) return;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (iq < lq) {
+        const float inv = 1.f / l_tot;
+        const int row = q_seg0 + iq;
+        char *orow = (char *)p.o + ((int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head) * 2;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                bf16x4 w;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o_acc[db][g4 * 4 + j] * inv);
+                *(bf16x4 *)(orow + (db * 32 + g4 * 8 + half * 4) * 2) = w;
+            }
+        if (half == 0)
+            p.lse[(int64_t)h * p.n_tokens + row] = m_run * 0.69314718055994530942f + __logf(l_tot);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s)
+{
+    // Upper bound on the number of 128-row tiles: sum_g ceil(Lq_g / BM) <= T / BM + n_segments.
+    const int64_t tiles_max = (int64_t)p.n_tokens / BM + p.n_segments;
+    const int64_t blocks = tiles_max * p.n_q_heads;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    mfma_fwd_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(p);
+    return hipGetLastError();
+}
+
+}  // namespace cf

@@ -209,20 +209,49 @@ __global__ __launch_bounds__(kWaves * 64) void simple_dkv_kernel(cf_attn_bwd_par
     }
 }
 
-// delta[h][t] = <dO, O>; one wavefront per (token, head).  When dq_acc is given, the same
-// wavefront also clears that token/head's row of the fp32 dQ accumulator.
+// delta[h][t] = <dO_t, O_t> = sum_j P_tj <dO_t, v_j>; one wavefront per (token, head).
+// The first form is used for almost every row.  O arrives rounded to the storage type, and for a
+// row that sees only a few keys (large P, large |O|) that rounding is the largest error of the whole
+// backward pass (it lands in dK of the first keys of each sequence).  Rows that see at most 64 keys
+// therefore use the second form, one key per lane, which needs no O at all.
+// When dq_acc is given, the same wavefront also clears that token/head's row of the fp32 dQ accumulator.
 template <typename T, int D>
 __global__ __launch_bounds__(kWaves * 64) void delta_kernel(cf_attn_bwd_params b, float *delta, float *dq_acc)
 {
     const cf_attn_fwd_params &p = b.f;
+    __shared__ float sq[kWaves][D], sdo[kWaves][D];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int row = blockIdx.x * kWaves + wave;
     if (row >= p.n_tokens) return;
     const int h = blockIdx.y;
     const T *o = (const T *)p.o + (int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head;
     const T *d_o = (const T *)b.d_o + (int64_t)row * b.do_stride_tok + (int64_t)h * b.do_stride_head;
+    const int g = find_segment(p.cu_seqlens_q, p.n_segments, row);
+    const int q0 = p.cu_seqlens_q[g], lq = p.cu_seqlens_q[g + 1] - q0;
+    const int k0 = p.cu_seqlens_k[g], lk = p.cu_seqlens_k[g + 1] - k0;
+    const int n_vis = lk - lq + (row - q0) + 1;
     float s = 0.f;
-    for (int t = 0; t < D / 64; ++t) s += ld(o + lane + 64 * t) * ld(d_o + lane + 64 * t);
+    if (n_vis <= 64) {
+        const int kh = h / (p.n_q_heads / p.n_kv_heads);
+        const T *q = (const T *)p.q + (int64_t)row * p.q_stride_tok + (int64_t)h * p.q_stride_head;
+        for (int t = 0; t < D / 64; ++t) {
+            sq[wave][lane + 64 * t] = ld(q + lane + 64 * t);
+            sdo[wave][lane + 64 * t] = ld(d_o + lane + 64 * t);
+        }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < n_vis) {
+            const T *kj = (const T *)p.k + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
+            const T *vj = (const T *)p.v + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
+            float sc = 0.f, dp = 0.f;
+            for (int x = 0; x < D; ++x) {
+                sc += sq[wave][x] * ld(kj + x);
+                dp += sdo[wave][x] * ld(vj + x);
+            }
+            s = expf(sc * p.softmax_scale - p.lse[(int64_t)h * p.n_tokens + row]) * dp;
+        }
+    } else {
+        for (int t = 0; t < D / 64; ++t) s += ld(o + lane + 64 * t) * ld(d_o + lane + 64 * t);
+    }
     s = wave_sum(s);
     if (lane == 0) delta[(int64_t)h * p.n_tokens + row] = s;
     if (dq_acc) {

@@ -1,0 +1,92 @@
+// Device-side helpers shared by the bf16 MFMA kernels (gfx950).
+//
+// MFMA 32x32x16 bf16 operand layout (lane l of a 64-wide wavefront, half = l / 32):
+//   A (M x K): lane holds row  m = l % 32, k = 8*half + 0..7        (bf16x8)
+//   B (K x N): lane holds col  n = l % 32, k = 8*half + 0..7        (bf16x8)
+//   C/D (M x N, fp32x16): lane holds col n = l % 32, register i <-> row (i/4)*8 + 4*half + i%4
+//
+// ds_read_tr16_b64 (transposing LDS read): inside each block of 16 lanes, lane r supplies the address
+// of 4 consecutive 16-bit elements; the 16x4 elements are handed out so that lane i receives
+// element (i % 4) of the rows supplied by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.  With lane r
+// pointing at mem[k0 + r/4][n0 + 4*(r%4)] (a 4 x 16 block of a row-major matrix), lane i therefore
+// gets mem[k0 + 0..3][n0 + i]: four consecutive k for one n -- half of an MFMA operand whose
+// contraction index runs along the matrix rows.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cf {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+#define CF_LDS __attribute__((address_space(3)))
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Two transposing reads, 8 rows apart... the caller passes both addresses; result is one bf16x8 operand.
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const char *lo_addr, const char *hi_addr)
+{
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CF_LDS s16x4 *)lo_addr);
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CF_LDS s16x4 *)hi_addr);
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const char *addr)
+{
+    return *(const bf16x8 *)addr;
+}
+
+// Packs 8 fp32 values into a bf16x8 (round to nearest even; v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, float a4, float a5, float a6,
+                                        float a7)
+{
+    bf16x8 r;
+    r[0] = (__bf16)a0; r[1] = (__bf16)a1; r[2] = (__bf16)a2; r[3] = (__bf16)a3;
+    r[4] = (__bf16)a4; r[5] = (__bf16)a5; r[6] = (__bf16)a6; r[7] = (__bf16)a7;
+    return r;
+}
+
+// Finds the tile a workgroup owns.  Tiles of `tile` rows are counted per segment over cu[0..n_seg]
+// and numbered from the LAST tile of the LAST segment backwards (the later tiles of a segment see more
+// keys, so the heaviest tiles get the lowest ranks and start first).  Every lane of every wavefront
+// computes the same answer.  Returns false if rank >= number of tiles.
+__device__ __forceinline__ bool locate_tile(const int32_t *cu, int n_seg, int tile, int rank, int &seg,
+                                            int &tile_in_seg)
+{
+    const int lane = threadIdx.x & 63;
+    for (int base = 0; base < n_seg; base += 64) {
+        const int gi = n_seg - 1 - (base + lane);
+        int cnt = 0;
+        if (gi >= 0) cnt = (cu[gi + 1] - cu[gi] + tile - 1) / tile;
+        int inc = cnt;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        const int total = __shfl(inc, 63);
+        if (rank < total) {
+            const unsigned long long ball = __ballot(inc > rank);
+            const int first = __ffsll((long long)ball) - 1;
+            const int exc = __shfl(inc - cnt, first);
+            const int c = __shfl(cnt, first);
+            seg = n_seg - 1 - (base + first);
+            tile_in_seg = c - 1 - (rank - exc);
+            return true;
+        }
+        rank -= total;
+    }
+    return false;
+}
+
+}  // namespace cf
