@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the ChunkFlow hot path on one MI355X.
+
+One step = chunk attention forward over every chunk of the batch (each dependency group ascending)
+followed by the backward over every chunk (each group descending, key/value gradients accumulated
+into the state), all through the C ABI, inputs resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6          # 256 CU x 4096 bf16 FLOP/clk/CU x 2.4 GHz (dense)
+WORKLOADS = {                       # name -> inputs.CONFIGS key
+    "config2_packed_8k": "packed_8k",
+    "config3_long32k_mixed": "long32k_mixed",
+}
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), scaled by the copy-kernel calibration; None until measured for this build.
+MEASURED_TRAFFIC_BYTES = {"config2_packed_8k": None, "config3_long32k_mixed": None}
+
+
+def cpu_baseline(lens, cfg, seed, budget_pairs):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: whole sequences taken
+    in batch order until their unmasked-pair count reaches the budget (about 10-30 s of CPU work)."""
+    import numpy as np
+    from oracle import attention as OA
+    from paper_2503_02356_amd import inputs
+    Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
+    scale = np.float32(1.0 / np.sqrt(D))
+    pairs, n_seq, secs = 0, 0, 0.0
+    for sid, L in enumerate(lens):
+        L = int(L)
+        if L > cfg["C"]:
+            continue                    # the sample is made of whole short sequences
+        v = inputs.seq_values(seed, sid, L, Hq, Hkv, D, cfg["dtype"])
+        t0 = time.perf_counter()
+        o, lse = OA.seq_attn_fwd(v["q"], v["k"], v["v"], scale)
+        OA.seq_attn_bwd(v["q"], v["k"], v["v"], o, lse, v["d_o"], scale)
+        secs += time.perf_counter() - t0
+        pairs += L * (L + 1) // 2
+        n_seq += 1
+        if pairs >= budget_pairs:
+            break
+    flop = 14.0 * D * Hq * pairs
+    return {"value": flop / secs / 1e12, "unit": "TFLOP/s", "cores": OA.num_threads(), "kind": "oracle",
+            "sample": f"first {n_seq} short sequences of the batch, {pairs} unmasked pairs, fwd+bwd fp64, {secs:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-pairs", type=float, default=6e6, help="unmasked pairs in the oracle's timed sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2503_02356_amd import binding as B
+    from paper_2503_02356_amd import inputs
+    from paper_2503_02356_amd.runner import ChunkAttention
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    cfg_key = WORKLOADS[args.workload]
+    cfg = inputs.CONFIGS[cfg_key]
+    Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
+
+    def count_chunks(lens, C):
+        p = B.cf_build_chunks(lens, C)
+        n = p.n_chunks
+        p.close()
+        return n
+    lens, C = inputs.seq_lens(cfg_key, args.seed, count_chunks)
+    t0 = time.perf_counter()
+    plan = B.cf_build_chunks(lens, C)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
+    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"]).load(vals)
+    pairs = eng.total_pairs
+    flop_step = 14.0 * D * Hq * pairs
+
+    def step():
+        eng.zero_grads()
+        eng.run_forward()
+        eng.run_backward()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    tflops = flop_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations with HIP events on the launch stream (same launches, second pass)
+    def kernel_ms(kind):
+        evs = []
+        order = eng.forward_order() if kind == "fwd" else eng.backward_order()
+        if kind == "bwd":
+            eng.zero_grads()
+        for c in order:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            B.cf_profile_next_call(e0, e1)
+            (B.cf_attn_fwd if kind == "fwd" else B.cf_attn_bwd)(eng.chunks[c][kind])
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+    reps = max(1, min(args.steps, 5))
+    fwd_ms = np.mean([kernel_ms("fwd") for _ in range(reps)], axis=0)
+    bwd_ms = np.mean([kernel_ms("bwd") for _ in range(reps)], axis=0)
+    n_chunks = len(eng.chunks)
+    bwd_flop_per_launch = 10.0 * D * Hq * pairs / n_chunks          # algorithmic FLOP of an average launch
+    bwd_avg_ms = float(np.mean(bwd_ms))
+    fwd_avg_ms = float(np.mean(fwd_ms))
+    achieved = bwd_flop_per_launch / (bwd_avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "mfma_bwd_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES[args.workload],
+                "avg_launch_ms": bwd_avg_ms, "launches_per_step": n_chunks,
+                "fwd_kernel": {"kernel": "mfma_fwd_kernel", "avg_launch_ms": fwd_avg_ms,
+                               "achieved": 4.0 * D * Hq * pairs / n_chunks / (fwd_avg_ms * 1e-3) / 1e12}}
+
+    out = {"metric": "chunk attention fwd+bwd TFLOP/s (unmasked pairs)", "value": tflops, "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": args.workload, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "chunk_size": C,
+                      "n_sequences": int(len(lens)), "n_chunks": n_chunks, "tokens": int(plan.total_tokens),
+                      "unmasked_pairs": int(pairs), "flop_per_step": flop_step, "seed": args.seed,
+                      "plan_build_ms": plan_ms},
+           "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
+           "roofline": roofline}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(lens, cfg, args.seed, args.cpu_pairs)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

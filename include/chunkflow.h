@@ -176,6 +176,15 @@ typedef struct {
 int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p);
 int cf_attn_bwd(const cf_attn_bwd_params *p, void *hip_stream);
 
+/*
+ * Measurement aid (not part of the paper's method): when both events (hipEvent_t, created by the
+ * caller with timing enabled) are non-NULL, the NEXT cf_attn_fwd / cf_attn_bwd call on this thread
+ * records `start` right before and `stop` right after its main kernel (forward: the attention
+ * kernel; backward: the dK/dV/dQ kernel, without the delta and dQ-convert kernels) on that call's
+ * stream, then the hook clears itself.  Passing NULLs clears it.  Never fails.
+ */
+int cf_profile_next_call(void *start_event, void *stop_event);
+
 /* Number of unmasked (query, key) pairs of a chunk described by HOST copies of its cu_seqlens:
  * sum over segments of Lq*(Lk-Lq) + Lq*(Lq+1)/2.  Used to turn run time into FLOP/s. */
 int64_t cf_count_pairs(const int32_t *cu_seqlens_q_host, const int32_t *cu_seqlens_k_host,

@@ -17,7 +17,7 @@ CF_FLAG_SCALAR_KERNELS = 1
 CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
 EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_plan_free", "cf_plan_get",
-           "cf_build_schedule", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_count_pairs"]
+           "cf_build_schedule", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_count_pairs", "cf_profile_next_call"]
 
 
 class CfError(RuntimeError):
@@ -82,6 +82,7 @@ def lib():
         L.cf_attn_bwd_workspace_bytes.argtypes = [C.POINTER(AttnFwdParams)]
         L.cf_attn_bwd_workspace_bytes.restype = C.c_int64
         L.cf_attn_bwd.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
+        L.cf_profile_next_call.argtypes = [C.c_void_p, C.c_void_p]
         L.cf_count_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.cf_count_pairs.restype = C.c_int64
         _lib = L
@@ -163,6 +164,15 @@ def cf_count_pairs(cu_q, cu_k):
     a = np.ascontiguousarray(cu_q, dtype=np.int32)
     b = np.ascontiguousarray(cu_k, dtype=np.int32)
     return _check(lib().cf_count_pairs(a.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p), len(a) - 1))
+
+
+def cf_profile_next_call(start_event, stop_event):
+    """torch.cuda.Event pair (enable_timing=True) recorded around the next call's main kernel."""
+    for e in (start_event, stop_event):
+        if e is not None and not e.cuda_event:      # torch creates the hipEvent lazily: force it
+            e.record()
+    lib().cf_profile_next_call(C.c_void_p(start_event.cuda_event) if start_event is not None else None,
+                               C.c_void_p(stop_event.cuda_event) if stop_event is not None else None)
 
 
 def _dtype_code(t):

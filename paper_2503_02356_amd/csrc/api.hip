@@ -45,17 +45,20 @@ int check_fwd(const cf_attn_fwd_params *p, const char *who, bool sizes_only)
     return CF_OK;
 }
 
-bool use_mfma(const cf_attn_fwd_params &p)
+// Shapes the MFMA kernels cover (decides the workspace size, so it may only look at sizes, dtype, flags).
+bool mfma_shape(const cf_attn_fwd_params &p)
 {
     return p.dtype == CF_BF16 && p.head_dim == 128 && !(p.flags & CF_FLAG_SCALAR_KERNELS);
 }
+// The MFMA kernels take the row maximum before scaling, which needs a positive scale.
+bool use_mfma(const cf_attn_fwd_params &p) { return mfma_shape(p) && p.softmax_scale > 0.f; }
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 int64_t delta_bytes(const cf_attn_fwd_params &p) { return round_up((int64_t)p.n_q_heads * p.n_tokens * 4, 256); }
 int64_t dq_acc_bytes(const cf_attn_fwd_params &p)
 {
-    return use_mfma(p) ? round_up((int64_t)p.n_tokens * p.n_q_heads * p.head_dim * 4, 256) : 0;
+    return mfma_shape(p) ? round_up((int64_t)p.n_tokens * p.n_q_heads * p.head_dim * 4, 256) : 0;
 }
 
 int hip_fail(const char *who, hipError_t e)
@@ -63,7 +66,23 @@ int hip_fail(const char *who, hipError_t e)
     return cf::fail(CF_EHIP, "%s: %s", who, hipGetErrorString(e));
 }
 
+thread_local cf::ProfileHook g_hook;
+
 }  // namespace
+
+cf::ProfileHook cf::take_profile_hook()
+{
+    cf::ProfileHook h = g_hook;
+    g_hook = cf::ProfileHook();
+    return h;
+}
+
+extern "C" int cf_profile_next_call(void *start_event, void *stop_event)
+{
+    g_hook.start = start_event && stop_event ? static_cast<hipEvent_t>(start_event) : nullptr;
+    g_hook.stop = start_event && stop_event ? static_cast<hipEvent_t>(stop_event) : nullptr;
+    return CF_OK;
+}
 
 extern "C" int cf_attn_fwd(const cf_attn_fwd_params *p, void *hip_stream)
 {
@@ -106,7 +125,7 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
                         (long long)need);
     cf::BwdWorkspace ws;
     ws.delta = static_cast<float *>(b->workspace);
-    ws.dq_acc = use_mfma(p) ? reinterpret_cast<float *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
+    ws.dq_acc = mfma_shape(p) ? reinterpret_cast<float *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = cf::launch_delta(*b, ws, s);
     if (e != hipSuccess) return hip_fail(who, e);

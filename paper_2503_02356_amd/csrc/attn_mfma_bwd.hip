@@ -311,8 +311,11 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     const int64_t tiles_max = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
     const int64_t blocks = tiles_max * p.n_kv_heads;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const ProfileHook hook = take_profile_hook();
+    if (hook.start) (void)hipEventRecord(hook.start, s);
     mfma_bwd_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(b, ws.delta, ws.dq_acc);
     hipError_t e = hipGetLastError();
+    if (hook.stop) (void)hipEventRecord(hook.stop, s);
     if (e != hipSuccess) return e;
     const int64_t n8 = (int64_t)p.n_tokens * p.n_q_heads * (D / 8);
     dq_convert_kernel<<<dim3((unsigned)((n8 + 255) / 256)), 256, 0, s>>>(b, ws.dq_acc);

@@ -213,8 +213,12 @@ hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s)
     const int64_t tiles_max = (int64_t)p.n_tokens / BM + p.n_segments;
     const int64_t blocks = tiles_max * p.n_q_heads;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const ProfileHook hook = take_profile_hook();
+    if (hook.start) (void)hipEventRecord(hook.start, s);
     mfma_fwd_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(p);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    return e;
 }
 
 }  // namespace cf

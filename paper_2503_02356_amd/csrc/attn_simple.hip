@@ -264,8 +264,12 @@ template <typename T, int D>
 hipError_t run_fwd(const cf_attn_fwd_params &p, hipStream_t s)
 {
     dim3 grid((p.n_tokens + kWaves - 1) / kWaves, p.n_q_heads);
+    const ProfileHook hook = take_profile_hook();
+    if (hook.start) (void)hipEventRecord(hook.start, s);
     simple_fwd_kernel<T, D><<<grid, kWaves * 64, 0, s>>>(p);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    return e;
 }
 
 template <typename T, int D>
@@ -273,12 +277,17 @@ hipError_t run_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStrea
 {
     const cf_attn_fwd_params &p = b.f;
     dim3 gq((p.n_tokens + kWaves - 1) / kWaves, p.n_q_heads);
+    const ProfileHook hook = take_profile_hook();
+    if (hook.start) (void)hipEventRecord(hook.start, s);
     simple_dq_kernel<T, D><<<gq, kWaves * 64, 0, s>>>(b, ws.delta);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    dim3 gk((p.n_kv_tokens + kWaves - 1) / kWaves, p.n_kv_heads);
-    simple_dkv_kernel<T, D><<<gk, kWaves * 64, 0, s>>>(b, ws.delta);
-    return hipGetLastError();
+    if (e == hipSuccess) {
+        dim3 gk((p.n_kv_tokens + kWaves - 1) / kWaves, p.n_kv_heads);
+        simple_dkv_kernel<T, D><<<gk, kWaves * 64, 0, s>>>(b, ws.delta);
+        e = hipGetLastError();
+    }
+    if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    return e;
 }
 
 template <typename T, int D>

@@ -14,6 +14,13 @@ struct BwdWorkspace {
     float *dq_acc;
 };
 
+// One-shot event pair recorded around the main kernel of the next launch on this thread (see
+// cf_profile_next_call); both NULL when unset.
+struct ProfileHook {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+ProfileHook take_profile_hook();
+
 // Plain scalar kernels: any supported head_dim, fp32 or bf16 storage, fp32 arithmetic.
 hipError_t launch_simple_fwd(const cf_attn_fwd_params &p, hipStream_t s);
 hipError_t launch_simple_bwd(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
