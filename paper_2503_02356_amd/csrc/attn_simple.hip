@@ -209,55 +209,73 @@ __global__ __launch_bounds__(kWaves * 64) void simple_dkv_kernel(cf_attn_bwd_par
     }
 }
 
-// delta[h][t] = <dO_t, O_t> = sum_j P_tj <dO_t, v_j>; one wavefront per (token, head).
-// The first form is used for almost every row.  O arrives rounded to the storage type, and for a
-// row that sees only a few keys (large P, large |O|) that rounding is the largest error of the whole
-// backward pass (it lands in dK of the first keys of each sequence).  Rows that see at most 64 keys
-// therefore use the second form, one key per lane, which needs no O at all.
-// When dq_acc is given, the same wavefront also clears that token/head's row of the fp32 dQ accumulator.
+// delta[h][t] = <dO_t, O_t>: 16 lanes per (token, head), 8 (or 4) consecutive d per lane and step.
 template <typename T, int D>
-__global__ __launch_bounds__(kWaves * 64) void delta_kernel(cf_attn_bwd_params b, float *delta, float *dq_acc)
+__global__ __launch_bounds__(256) void delta_kernel(cf_attn_bwd_params b, float *delta)
+{
+    const cf_attn_fwd_params &p = b.f;
+    const int64_t pair = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);   // (token, head) pair
+    const int sub = threadIdx.x & 15;
+    float s = 0.f;
+    int64_t row = 0, h = 0;
+    const bool live = pair < (int64_t)p.n_tokens * p.n_q_heads;
+    if (live) {
+        row = pair / p.n_q_heads;
+        h = pair % p.n_q_heads;
+        const T *o = (const T *)p.o + row * p.o_stride_tok + h * p.o_stride_head;
+        const T *d_o = (const T *)b.d_o + row * b.do_stride_tok + h * b.do_stride_head;
+        constexpr int V = 16 / sizeof(T);   // elements per 16-byte load
+        for (int d0 = sub * V; d0 < D; d0 += 16 * V) {
+            const uint4 a = *(const uint4 *)(o + d0), c = *(const uint4 *)(d_o + d0);
+            const T *pa = (const T *)&a, *pc = (const T *)&c;
+#pragma unroll
+            for (int j = 0; j < V; ++j) s += ld(pa + j) * ld(pc + j);
+        }
+    }
+    for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if (live && sub == 0) delta[h * p.n_tokens + row] = s;
+}
+
+// O arrives rounded to the storage type, and for a row that sees only a few keys (large P, large |O|)
+// that rounding would be the largest error of the whole backward pass (it lands in dK of the first keys of
+// each sequence).  Rows that see at most 64 keys therefore get delta = sum_j P_tj <dO_t, v_j> instead,
+// one key per lane, which needs no O at all.  One wavefront per (segment, one of its first 64 rows, head);
+// runs after delta_kernel and overwrites its value for those rows.
+template <typename T, int D>
+__global__ __launch_bounds__(kWaves * 64) void delta_head_rows_kernel(cf_attn_bwd_params b, float *delta)
 {
     const cf_attn_fwd_params &p = b.f;
     __shared__ float sq[kWaves][D], sdo[kWaves][D];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int row = blockIdx.x * kWaves + wave;
-    if (row >= p.n_tokens) return;
+    const int g = blockIdx.x / (64 / kWaves);
+    const int i = (blockIdx.x % (64 / kWaves)) * kWaves + wave;        // row inside the segment, 0..63
     const int h = blockIdx.y;
-    const T *o = (const T *)p.o + (int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head;
-    const T *d_o = (const T *)b.d_o + (int64_t)row * b.do_stride_tok + (int64_t)h * b.do_stride_head;
-    const int g = find_segment(p.cu_seqlens_q, p.n_segments, row);
     const int q0 = p.cu_seqlens_q[g], lq = p.cu_seqlens_q[g + 1] - q0;
     const int k0 = p.cu_seqlens_k[g], lk = p.cu_seqlens_k[g + 1] - k0;
-    const int n_vis = lk - lq + (row - q0) + 1;
+    const int n_vis = lk - lq + i + 1;
+    if (i >= lq || n_vis > 64) return;   // whole wavefront leaves together; only wave-level barriers below
+    const int row = q0 + i;
+    const int kh = h / (p.n_q_heads / p.n_kv_heads);
+    const T *q = (const T *)p.q + (int64_t)row * p.q_stride_tok + (int64_t)h * p.q_stride_head;
+    const T *d_o = (const T *)b.d_o + (int64_t)row * b.do_stride_tok + (int64_t)h * b.do_stride_head;
+    for (int t = 0; t < D / 64; ++t) {
+        sq[wave][lane + 64 * t] = ld(q + lane + 64 * t);
+        sdo[wave][lane + 64 * t] = ld(d_o + lane + 64 * t);
+    }
+    __builtin_amdgcn_wave_barrier();
     float s = 0.f;
-    if (n_vis <= 64) {
-        const int kh = h / (p.n_q_heads / p.n_kv_heads);
-        const T *q = (const T *)p.q + (int64_t)row * p.q_stride_tok + (int64_t)h * p.q_stride_head;
-        for (int t = 0; t < D / 64; ++t) {
-            sq[wave][lane + 64 * t] = ld(q + lane + 64 * t);
-            sdo[wave][lane + 64 * t] = ld(d_o + lane + 64 * t);
+    if (lane < n_vis) {
+        const T *kj = (const T *)p.k + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
+        const T *vj = (const T *)p.v + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
+        float sc = 0.f, dp = 0.f;
+        for (int x = 0; x < D; ++x) {
+            sc += sq[wave][x] * ld(kj + x);
+            dp += sdo[wave][x] * ld(vj + x);
         }
-        __builtin_amdgcn_wave_barrier();
-        if (lane < n_vis) {
-            const T *kj = (const T *)p.k + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
-            const T *vj = (const T *)p.v + (int64_t)(k0 + lane) * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head;
-            float sc = 0.f, dp = 0.f;
-            for (int x = 0; x < D; ++x) {
-                sc += sq[wave][x] * ld(kj + x);
-                dp += sdo[wave][x] * ld(vj + x);
-            }
-            s = expf(sc * p.softmax_scale - p.lse[(int64_t)h * p.n_tokens + row]) * dp;
-        }
-    } else {
-        for (int t = 0; t < D / 64; ++t) s += ld(o + lane + 64 * t) * ld(d_o + lane + 64 * t);
+        s = expf(sc * p.softmax_scale - p.lse[(int64_t)h * p.n_tokens + row]) * dp;
     }
     s = wave_sum(s);
     if (lane == 0) delta[(int64_t)h * p.n_tokens + row] = s;
-    if (dq_acc) {
-        float *a = dq_acc + ((int64_t)row * p.n_q_heads + h) * D;
-        for (int t = 0; t < D / 64; ++t) a[lane + 64 * t] = 0.f;
-    }
 }
 
 template <typename T, int D>
@@ -293,8 +311,12 @@ hipError_t run_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStrea
 template <typename T, int D>
 hipError_t run_delta(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStream_t s)
 {
-    dim3 grid((b.f.n_tokens + kWaves - 1) / kWaves, b.f.n_q_heads);
-    delta_kernel<T, D><<<grid, kWaves * 64, 0, s>>>(b, ws.delta, ws.dq_acc);
+    const int64_t pairs = (int64_t)b.f.n_tokens * b.f.n_q_heads;
+    delta_kernel<T, D><<<dim3((unsigned)((pairs + 15) / 16)), 256, 0, s>>>(b, ws.delta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    dim3 grid(b.f.n_segments * (64 / kWaves), b.f.n_q_heads);
+    delta_head_rows_kernel<T, D><<<grid, kWaves * 64, 0, s>>>(b, ws.delta);
     return hipGetLastError();
 }
 

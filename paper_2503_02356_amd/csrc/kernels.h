@@ -6,12 +6,9 @@
 
 namespace cf {
 
-// Backward scratch layout inside the caller's workspace (all fp32):
-//   delta   [Hq][T]         rowsum(dO * O)
-//   dq_acc  [T][Hq][D]      bf16 MFMA path only: fp32 accumulation target of dQ
+// Backward scratch inside the caller's workspace: delta [Hq][T] fp32 = rowsum(dO * O).
 struct BwdWorkspace {
     float *delta;
-    float *dq_acc;
 };
 
 // One-shot event pair recorded around the main kernel of the next launch on this thread (see
@@ -25,7 +22,7 @@ ProfileHook take_profile_hook();
 hipError_t launch_simple_fwd(const cf_attn_fwd_params &p, hipStream_t s);
 hipError_t launch_simple_bwd(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
 
-// delta[h][t] = sum_d dO[t][h][d] * O[t][h][d]; optionally zero-fills dq_acc on the way.
+// delta[h][t] = sum_d dO[t][h][d] * O[t][h][d].
 hipError_t launch_delta(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
 
 // bf16 MFMA kernels, head_dim 128.

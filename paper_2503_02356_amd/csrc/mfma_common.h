@@ -57,6 +57,14 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
     return r;
 }
 
+// Swizzled LDS tile with 256-byte rows (128 bf16) and no padding: the 16-byte unit u of row r lives at
+// unit u ^ swz(r).  LDS has 64 four-byte banks; a 16-byte row read (ds_read_b128) is served 16 lanes per
+// clock and a transposing 8-byte read (ds_read_b64_tr_b16) 32 lanes per clock.  swz() maps 16 consecutive
+// rows to 16 different units (row reads of one column by 16 rows are conflict free) AND gives the 4
+// consecutive rows of a transposing read 4 different groups of 4 units (those are conflict free too).
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+__device__ __forceinline__ int tile_off(int row, int unit) { return row * 256 + ((unit ^ swz(row)) << 4); }
+
 // Finds the tile a workgroup owns.  Tiles of `tile` rows are counted per segment over cu[0..n_seg]
 // and numbered from the LAST tile of the LAST segment backwards (the later tiles of a segment see more
 // keys, so the heaviest tiles get the lowest ranks and start first).  Every lane of every wavefront

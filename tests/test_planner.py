@@ -112,7 +112,7 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     p.n_kv_tokens = 16
     assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL          # NULL pointers
     assert b"NULL" in B.lib().cf_last_error()
-    assert B.cf_attn_bwd_workspace_bytes(p) >= 4 * 16 * 4 + 16 * 4 * 128 * 4
+    assert B.cf_attn_bwd_workspace_bytes(p) >= 4 * 16 * 4
     b = B.AttnBwdParams()
     assert B.lib().cf_attn_bwd(None, None) == B.CF_EINVAL
     assert B.lib().cf_attn_bwd(ctypes.byref(b), None) < 0
