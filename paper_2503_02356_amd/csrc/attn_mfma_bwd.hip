@@ -45,18 +45,20 @@ constexpr int DKV_STAGE_BYTES = 2 * QTILE_BYTES + 512;  // Q, dO, LSE[64], delta
 constexpr int TROW = 132;   // floats per row of the end-of-kernel transpose scratch (128 + 4)
 constexpr int DKV_SMEM_BYTES = 2 * DKV_STAGE_BYTES > 4 * 32 * TROW * 4 ? 2 * DKV_STAGE_BYTES : 4 * 32 * TROW * 4;
 
-struct QTileRegs {
-    i32x4 q[4], d_o[4];
-    float stat;
-};
-
-template <bool FUSED_HEADS>
+// HEAD_TILES = false: the main launch.  It leaves out the tile pairs made of a sequence's first 128
+//     positions (query rows at positions < 128 x key tile 0): those rows see few keys, their P and dS are
+//     large, and the bf16 rounding of P and dS would be the largest error in dK/dV.
+// HEAD_TILES = true : a small second launch, one workgroup per (segment, head), that does exactly those
+//     tile pairs and feeds the MFMAs the bf16 values AND their bf16 rounding residuals.
+template <bool FUSED_HEADS, bool HEAD_TILES>
 __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta)
 {
     const cf_attn_fwd_params &p = b.f;
+    // Two separate stage arrays: see the forward kernel.  The end-of-kernel transpose scratch spans both.
     __shared__ __attribute__((aligned(16))) char smem[DKV_SMEM_BYTES];
+    char *const stage_a = smem, *const stage_b = smem + DKV_STAGE_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, col = lane & 31, r16 = lane & 15, blk = (lane >> 4) & 1;
+    const int half = lane >> 5, col = lane & 31;
 
     // Block id -> (key tile rank, head); the key/value head varies fastest (XCD L2 locality, see forward).
     const int G = p.n_q_heads / p.n_kv_heads;
@@ -67,17 +69,25 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
     const int n_heads = FUSED_HEADS ? G : 1;
     const int rank = FUSED_HEADS ? id : id / G;
 
-    int seg, t_rev;
-    if (!locate_tile(p.cu_seqlens_k, p.n_segments, BKV, rank, seg, t_rev)) return;
+    int seg, t_rev = 0;
+    if (HEAD_TILES) {
+        seg = rank;                                  // grid = n_segments x heads
+        if (seg >= p.n_segments) return;
+    } else if (!locate_tile(p.cu_seqlens_k, p.n_segments, BKV, rank, seg, t_rev)) {
+        return;
+    }
     const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
     const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
     const int off = lk - lq;
     // locate_tile numbers tiles from the end; the FIRST key tiles of a segment are seen by the most rows,
     // so flip the order inside the segment to start the heaviest tiles first.
-    const int kt0 = ((lk + BKV - 1) / BKV - 1 - t_rev) * BKV;
+    const int kt0 = HEAD_TILES ? 0 : ((lk + BKV - 1) / BKV - 1 - t_rev) * BKV;
     const int i_min = max(0, kt0 - off);             // first query row that sees any key of this tile
-    const int qt_first = i_min / BQ;
-    const int n_qt = (lq + BQ - 1) / BQ - qt_first;  // >= 1 because kt0 < lk = lq + off
+    // query tiles whose rows sit at positions < 128 of the sequence (only key tile 0 can see them)
+    const int n_head_qt = off < 128 ? min((lq + BQ - 1) / BQ, (128 - off + BQ - 1) / BQ) : 0;
+    const int qt_first = HEAD_TILES ? 0 : (kt0 == 0 ? n_head_qt : i_min / BQ);
+    const int n_qt = HEAD_TILES ? n_head_qt : (lq + BQ - 1) / BQ - qt_first;
+    if (n_qt <= 0) return;                           // whole workgroup leaves before any barrier
     const int n_iter = n_heads * n_qt;
 
     const int kv_idx = kt0 + 32 * wave + col;        // this lane's key (segment-local)
@@ -102,78 +112,57 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
 #pragma unroll
         for (int j = 0; j < 16; ++j) dk[i][j] = dv[i][j] = 0.f;
 
-    // tile staging: 256 threads x 4 x 16 bytes for Q and for dO; threads 0..63 LSE, 64..127 delta
-    auto load_tile = [&](QTileRegs &r, int it) {
+    const LaneOffsets lo = lane_offsets();
+
+    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles; LSE (as
+    // log2, +inf for rows past the segment so that P = 0) and delta (0 there) go through one register of
+    // threads 0..63 / 64..127.
+    auto issue_tile = [&](int it, char *stage, float &stat) {
         const int h = h_first + it / n_qt;
         const int q0 = (qt_first + it % n_qt) * BQ;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int idx = tid + 256 * c;
-            const int64_t row = q_seg0 + min(q0 + (idx >> 4), lq - 1);
-            r.q[c] = *(const i32x4 *)((const char *)p.q + (row * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2 +
-                                      (idx & 15) * 16);
-            r.d_o[c] = *(const i32x4 *)((const char *)b.d_o +
-                                        (row * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2 + (idx & 15) * 16);
-        }
+        const int64_t row0 = q_seg0 + q0;
+        dma_tile<BQ>((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2, p.q_stride_tok * 2,
+                     lq - 1 - q0, stage);
+        dma_tile<BQ>((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2,
+                     b.do_stride_tok * 2, lq - 1 - q0, stage + QTILE_BYTES);
         if (tid < 128) {
             const int i = q0 + (tid & 63);
             const int64_t at = (int64_t)h * p.n_tokens + q_seg0 + min(i, lq - 1);
-            // rows past the segment get LSE = +inf (P = 0) and delta = 0
-            if (tid < 64) r.stat = i < lq ? p.lse[at] * kLog2e : INFINITY;
-            else r.stat = i < lq ? delta[at] : 0.f;
+            if (tid < 64) stat = i < lq ? p.lse[at] * kLog2e : INFINITY;
+            else stat = i < lq ? delta[at] : 0.f;
         }
     };
-    auto store_tile = [&](const QTileRegs &r, int buf) {
-        char *st = smem + buf * DKV_STAGE_BYTES;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int idx = tid + 256 * c;
-            const int o = tile_off(idx >> 4, idx & 15);
-            *(i32x4 *)(st + o) = r.q[c];
-            *(i32x4 *)(st + QTILE_BYTES + o) = r.d_o[c];
-        }
-        if (tid < 128) ((float *)(st + 2 * QTILE_BYTES))[tid] = r.stat;
+    auto publish_stats = [&](char *stage, float stat) {
+        if (tid < 128) ((float *)(stage + 2 * QTILE_BYTES))[tid] = stat;
     };
 
-    QTileRegs regs;
-    load_tile(regs, 0);
-    store_tile(regs, 0);
+    float stat = 0.f;
+    issue_tile(0, stage_a, stat);
+    publish_stats(stage_a, stat);
+    wait_lds_dma();
     __syncthreads();
 
-    for (int it = 0; it < n_iter; ++it) {
+    auto do_tile = [&](int it, const char *qs, char *next_stage) {
         const int q0 = (qt_first + it % n_qt) * BQ;
-        const char *qs = smem + (it & 1) * DKV_STAGE_BYTES;
         const char *dos = qs + QTILE_BYTES;
         const float *lse_s = (const float *)(qs + 2 * QTILE_BYTES);
         const float *del_s = lse_s + 64;
         const bool more = it + 1 < n_iter;
-        if (more) load_tile(regs, it + 1);
+        if (more) issue_tile(it + 1, next_stage, stat);
 
-        // S = Q K_w^T and dP = dO V_w^T for the tile's two 32-row blocks
-        f32x16 s[2], dp[2];
+        const bool need_mask = kt0 + BKV - 1 > q0 + off;
+        // The tile's two 32-row blocks one after the other (keeps S, dP, P, dS of only one block live).
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
+            // S = Q K_w^T and dP = dO V_w^T
+            f32x16 s, dp;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s[mb][j] = dp[mb][j] = 0.f;
-            const int row = mb * 32 + col;
+            for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                s[mb] = mfma32(lds_read_b128(qs + tile_off(row, 2 * ks + half)), kf[ks], s[mb]);
+            for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]), kf[ks], s);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                dp[mb] = mfma32(lds_read_b128(dos + tile_off(row, 2 * ks + half)), vf[ks], dp[mb]);
-        }
-        // P and dS (register i of block mb is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key)
-        const bool need_mask = kt0 + BKV - 1 > q0 + off;
-        // Rows among the first 128 positions of a sequence see few keys, so their P and dS are large and
-        // their bf16 rounding would be the largest error in dK/dV; those tiles add the rounding residuals.
-#ifdef EXP_NO_PRECISE
-        const bool precise = false;
-#else
-        const bool precise = kt0 == 0 && q0 + off < 128;
-#endif
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]), vf[ks], dp);
+            // P and dS: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int rbase = mb * 32 + g4 * 8 + half * 4;
@@ -182,99 +171,83 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int i = g4 * 4 + j;
-                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][i], c2, -l4[j]));
+                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[j]));
                     if (need_mask && kv_idx > q0 + rbase + j + off) pv = 0.f;
-                    s[mb][i] = pv;
-                    dp[mb][i] = pv * (dp[mb][i] - d4[j]);
+                    s[i] = pv;
+                    dp[i] = pv * (dp[i] - d4[j]);
                 }
             }
-        // dV_w^T += dO^T P and dK_w^T += Q^T dS : contraction over the 64 query rows in 4 groups of 16
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+            // dV_w^T += dO^T P and dK_w^T += Q^T dS : contraction over these 32 query rows in 2 groups of 16
 #pragma unroll
             for (int tq = 0; tq < 2; ++tq) {
-                const bf16x8 pb = pack8(s[mb][8 * tq + 0], s[mb][8 * tq + 1], s[mb][8 * tq + 2], s[mb][8 * tq + 3],
-                                        s[mb][8 * tq + 4], s[mb][8 * tq + 5], s[mb][8 * tq + 6], s[mb][8 * tq + 7]);
-                const bf16x8 dsb = pack8(dp[mb][8 * tq + 0], dp[mb][8 * tq + 1], dp[mb][8 * tq + 2], dp[mb][8 * tq + 3],
-                                         dp[mb][8 * tq + 4], dp[mb][8 * tq + 5], dp[mb][8 * tq + 6], dp[mb][8 * tq + 7]);
-                // k-slot 8*half + j is query row 32*mb + 16*tq + (j/4)*8 + 4*half + j%4:
-                // first transposing read rows r_lo .. r_lo+3 (by lane group), second 8 rows further
-                const int r_lo = mb * 32 + 16 * tq + 4 * half + (r16 >> 2), r_hi = r_lo + 8;
-                const int sub = 8 * (r16 & 1), u0 = 2 * blk + ((r16 >> 1) & 1);
+                const bf16x8 pb = pack8(s[8 * tq + 0], s[8 * tq + 1], s[8 * tq + 2], s[8 * tq + 3],
+                                        s[8 * tq + 4], s[8 * tq + 5], s[8 * tq + 6], s[8 * tq + 7]);
+                const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
+                                         dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
+                // k-slot 8*half + e is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
+                const int ta = mb * 8192 + tq * 4096;
 #pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const int o_lo = tile_off(r_lo, 4 * db + u0) + sub, o_hi = tile_off(r_hi, 4 * db + u0) + sub;
-                    dv[db] = mfma32(lds_read_tr_pair(dos + o_lo, dos + o_hi), pb, dv[db]);
-                    dk[db] = mfma32(lds_read_tr_pair(qs + o_lo, qs + o_hi), dsb, dk[db]);
+                for (int j = 0; j < 4; ++j) {
+                    dv[j] = mfma32(lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]), pb, dv[j]);
+                    dk[j] = mfma32(lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]), dsb, dk[j]);
                 }
-                if (precise) {
+                if (HEAD_TILES) {   // add the bf16 rounding residuals of P and dS
                     bf16x8 pl, dl;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        pl[j] = (__bf16)(s[mb][8 * tq + j] - (float)pb[j]);
-                        dl[j] = (__bf16)(dp[mb][8 * tq + j] - (float)dsb[j]);
+                    for (int e = 0; e < 8; ++e) {
+                        pl[e] = (__bf16)(s[8 * tq + e] - (float)pb[e]);
+                        dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
                     }
-#pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const int o_lo = tile_off(r_lo, 4 * db + u0) + sub, o_hi = tile_off(r_hi, 4 * db + u0) + sub;
-                        dv[db] = mfma32(lds_read_tr_pair(dos + o_lo, dos + o_hi), pl, dv[db]);
-                        dk[db] = mfma32(lds_read_tr_pair(qs + o_lo, qs + o_hi), dl, dk[db]);
-                    }
-                }
-            }
-        if (more) store_tile(regs, (it + 1) & 1);
-        __syncthreads();
-    }
-
-    // dK, dV: lane = key row, register group g4 of block db = 4 consecutive d starting at 32*db + 8*g4 + 4*half
-    if (FUSED_HEADS) {   // only writer of these rows in this launch: plain read-modify-write
-        if (kv_idx < lk) {
-            const int64_t row = k_seg0 + kv_idx;
-            float *gk = b.d_k + row * b.dkv_stride_tok + (int64_t)kh * b.dkv_stride_head;
-            float *gv = b.d_v + row * b.dkv_stride_tok + (int64_t)kh * b.dkv_stride_head;
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    const int d0 = db * 32 + g4 * 8 + half * 4;
-                    f32x4 a = *(f32x4 *)(gk + d0), c = *(f32x4 *)(gv + d0);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        a[j] += dk[db][g4 * 4 + j] * p.softmax_scale;
-                        c[j] += dv[db][g4 * 4 + j];
+                        dv[j] = mfma32(lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]), pl, dv[j]);
+                        dk[j] = mfma32(lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]), dl, dk[j]);
                     }
-                    *(f32x4 *)(gk + d0) = a;
-                    *(f32x4 *)(gv + d0) = c;
                 }
-        }
-    } else {
-        // The query heads of a group add into the same rows: fp32 atomics.  A lane-per-row atomic touches
-        // 64 cache lines per instruction, so each wavefront first turns its 32 x 128 block around in LDS
-        // (its own 16.5 KB slice of the workgroup's LDS, free after the loop's last barrier) and then adds
-        // whole rows: 64 lanes = 64 consecutive floats.
-        float *tr = (float *)smem + wave * 32 * TROW;
-        const int rows_valid = min(32, lk - (kt0 + 32 * wave));      // <= 0: this wavefront has no real keys
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
-#pragma unroll
-            for (int db = 0; db < 4; ++db)
-#pragma unroll
-                for (int g4 = 0; g4 < 4; ++g4) {
-                    f32x4 a;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        a[j] = which == 0 ? dk[db][g4 * 4 + j] * p.softmax_scale : dv[db][g4 * 4 + j];
-                    *(f32x4 *)(tr + col * TROW + db * 32 + g4 * 8 + half * 4) = a;
-                }
-            __builtin_amdgcn_wave_barrier();
-            float *gbase = (which == 0 ? b.d_k : b.d_v) + (int64_t)(k_seg0 + kt0 + 32 * wave) * b.dkv_stride_tok +
-                           (int64_t)kh * b.dkv_stride_head;
-            for (int r = 0; r < rows_valid; ++r) {
-                unsafeAtomicAdd(gbase + (int64_t)r * b.dkv_stride_tok + lane, tr[r * TROW + lane]);
-                unsafeAtomicAdd(gbase + (int64_t)r * b.dkv_stride_tok + 64 + lane, tr[r * TROW + 64 + lane]);
             }
-            __builtin_amdgcn_wave_barrier();
         }
+        if (more) publish_stats(next_stage, stat);
+        wait_lds_dma();
+        __syncthreads();
+    };
+    for (int it = 0; it < n_iter; it += 2) {
+        do_tile(it, stage_a, stage_b);
+        if (it + 1 < n_iter) do_tile(it + 1, stage_b, stage_a);
+    }
+
+    // dK, dV: lane = key row; register group g4 of accumulator j = 4 consecutive d starting at 32*j + 8*g4 + 4*half.
+    // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB slice, free after the loop's last
+    // barrier) and then updates whole rows, 64 lanes = 64 consecutive floats: a lane-per-row update would
+    // touch 64 cache lines per instruction.
+    //   FUSED_HEADS : this workgroup is the only writer of these rows in this launch: plain load, add, store.
+    //   otherwise   : the query heads of a group add into the same rows: fp32 atomic adds.
+    float *tr = (float *)smem + wave * 32 * TROW;
+    const int rows_valid = min(32, lk - (kt0 + 32 * wave));      // <= 0: this wavefront has no real keys
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                f32x4 a;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[e] = which == 0 ? dk[j][g4 * 4 + e] * p.softmax_scale : dv[j][g4 * 4 + e];
+                *(f32x4 *)(tr + col * TROW + j * 32 + g4 * 8 + half * 4) = a;
+            }
+        __builtin_amdgcn_wave_barrier();
+        float *gbase = (which == 0 ? b.d_k : b.d_v) + (int64_t)(k_seg0 + kt0 + 32 * wave) * b.dkv_stride_tok +
+                       (int64_t)kh * b.dkv_stride_head;
+        for (int r = 0; r < rows_valid; ++r) {
+            float *g = gbase + (int64_t)r * b.dkv_stride_tok;
+            if (FUSED_HEADS) {
+                g[lane] += tr[r * TROW + lane];
+                g[64 + lane] += tr[r * TROW + 64 + lane];
+            } else {
+                unsafeAtomicAdd(g + lane, tr[r * TROW + lane]);
+                unsafeAtomicAdd(g + 64 + lane, tr[r * TROW + 64 + lane]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -286,16 +259,18 @@ constexpr int BN = 64;                       // key rows per tile
 constexpr int KVTILE_BYTES = BN * 256;       // one swizzled K or V tile
 constexpr int DQ_STAGE_BYTES = 2 * KVTILE_BYTES;
 
-struct KVTileRegs {
-    i32x4 k[4], v[4];
-};
-
+// HEAD_TILES as in the dK/dV kernel: the main launch skips the 128-row tile that starts a sequence (rows at
+// positions < 128); the second launch (one workgroup per (segment, head)) does it with dS residuals.
+template <bool HEAD_TILES>
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, const float *__restrict__ delta)
 {
     const cf_attn_fwd_params &p = b.f;
-    __shared__ __attribute__((aligned(16))) char smem[2 * DQ_STAGE_BYTES];
+    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
+    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
+    __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5, col = lane & 31, r16 = lane & 15, blk = (lane >> 4) & 1;
+    const int half = lane >> 5, col = lane & 31;
 
     const int G = p.n_q_heads / p.n_kv_heads;
     int id = blockIdx.x;
@@ -304,12 +279,19 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     const int h = kh * G + id % G;
     const int rank = id / G;
 
-    int seg, tile_in_seg;
-    if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) return;
+    int seg, tile_in_seg = 0;
+    if (HEAD_TILES) {
+        seg = rank;                                  // grid = n_segments x heads
+        if (seg >= p.n_segments) return;
+    } else if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) {
+        return;
+    }
     const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
     const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
     const int off = lk - lq;
     const int q_tile0 = tile_in_seg * BM;
+    // the tile whose rows sit among the first 128 positions of a sequence belongs to the HEAD_TILES launch
+    if ((q_tile0 + off < 128) != HEAD_TILES) return;
     const int rows_valid = min(BM, lq - q_tile0);
     const int kmax = q_tile0 + rows_valid + off;     // keys [0, kmax) are visible to some row of the tile
     const int n_tiles = (kmax + BN - 1) / BN;
@@ -318,8 +300,6 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     const bool wave_active = wq0 < lq;
     const int iq = wq0 + col;                        // this lane's query row
     const int amax = iq + off;                       // last visible key of this lane's row
-    // rows among the first 128 positions of a sequence: carry dS as bf16 value + bf16 residual
-    const bool precise = q_tile0 + off < 128;
 
     const int64_t kv_row_bytes = p.kv_stride_tok * 2;
     const char *kbase = (const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
@@ -342,44 +322,27 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     }
     const float c2 = p.softmax_scale * kLog2e;
 
+    const LaneOffsets lo = lane_offsets();
     f32x16 dq[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 16; ++j) dq[i][j] = 0.f;
 
-    auto load_tile = [&](KVTileRegs &r, int tile_start) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int idx = tid + 256 * c;
-            const int row = min(tile_start + (idx >> 4), lk - 1);
-            const int64_t o = (int64_t)row * kv_row_bytes + (idx & 15) * 16;
-            r.k[c] = *(const i32x4 *)(kbase + o);
-            r.v[c] = *(const i32x4 *)(vbase + o);
-        }
+    auto issue_tile = [&](int tile_start, char *stage) {
+        const char *ksrc = kbase + (int64_t)tile_start * kv_row_bytes, *vsrc = vbase + (int64_t)tile_start * kv_row_bytes;
+        dma_tile<BN>(ksrc, kv_row_bytes, lk - 1 - tile_start, stage);
+        dma_tile<BN>(vsrc, kv_row_bytes, lk - 1 - tile_start, stage + KVTILE_BYTES);
     };
-    auto store_tile = [&](const KVTileRegs &r, char *stage) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int idx = tid + 256 * c;
-            const int o = tile_off(idx >> 4, idx & 15);
-            *(i32x4 *)(stage + o) = r.k[c];
-            *(i32x4 *)(stage + KVTILE_BYTES + o) = r.v[c];
-        }
-    };
-
-    KVTileRegs regs;
-    load_tile(regs, 0);
-    store_tile(regs, smem);
+    issue_tile(0, stage_a);
+    wait_lds_dma();
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
+    auto do_tile = [&](int t, const char *stage, char *next_stage) {
         const int tile_start = t * BN;
-        char *stage = smem + (t & 1) * DQ_STAGE_BYTES;
         const char *ks_ = stage;
         const char *vs_ = stage + KVTILE_BYTES;
-        const bool more = t + 1 < n_tiles;
-        if (more) load_tile(regs, tile_start + BN);
+        if (t + 1 < n_tiles) issue_tile(tile_start + BN, next_stage);
 
         if (wave_active && tile_start < wave_kmax) {
             const bool need_mask = tile_start + BN - 1 > wq0 + off;
@@ -389,13 +352,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
                 f32x16 s, dp;
 #pragma unroll
                 for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
-                const int row = mb * 32 + col;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    s = mfma32(lds_read_b128(ks_ + tile_off(row, 2 * ks + half)), qf[ks], s);
+                    s = mfma32(lds_read_b128(ks_ + mb * 8192 + lo.row_unit[ks]), qf[ks], s);
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    dp = mfma32(lds_read_b128(vs_ + tile_off(row, 2 * ks + half)), dof[ks], dp);
+                    dp = mfma32(lds_read_b128(vs_ + mb * 8192 + lo.row_unit[ks]), dof[ks], dp);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
@@ -407,41 +369,40 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
                 for (int tq = 0; tq < 2; ++tq) {
                     const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
                                              dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
-                    const int r_lo = mb * 32 + 16 * tq + 4 * half + (r16 >> 2), r_hi = r_lo + 8;
-                    const int sub = 8 * (r16 & 1), u0 = 2 * blk + ((r16 >> 1) & 1);
+                    const char *ka = ks_ + mb * 8192 + tq * 4096;
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const int o_lo = tile_off(r_lo, 4 * db + u0) + sub, o_hi = tile_off(r_hi, 4 * db + u0) + sub;
-                        dq[db] = mfma32(lds_read_tr_pair(ks_ + o_lo, ks_ + o_hi), dsb, dq[db]);
-                    }
-                    if (precise) {
+                    for (int j = 0; j < 4; ++j)
+                        dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dsb, dq[j]);
+                    if (HEAD_TILES) {   // add the bf16 rounding residual of dS
                         bf16x8 dl;
 #pragma unroll
-                        for (int j = 0; j < 8; ++j) dl[j] = (__bf16)(dp[8 * tq + j] - (float)dsb[j]);
+                        for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
 #pragma unroll
-                        for (int db = 0; db < 4; ++db) {
-                            const int o_lo = tile_off(r_lo, 4 * db + u0) + sub, o_hi = tile_off(r_hi, 4 * db + u0) + sub;
-                            dq[db] = mfma32(lds_read_tr_pair(ks_ + o_lo, ks_ + o_hi), dl, dq[db]);
-                        }
+                        for (int j = 0; j < 4; ++j)
+                            dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dl, dq[j]);
                     }
                 }
             }
         }
-        if (more) store_tile(regs, smem + ((t + 1) & 1) * DQ_STAGE_BYTES);
+        wait_lds_dma();
         __syncthreads();
+    };
+    for (int t = 0; t < n_tiles; t += 2) {
+        do_tile(t, stage_a, stage_b);
+        if (t + 1 < n_tiles) do_tile(t + 1, stage_b, stage_a);
     }
 
     if (wave_active && iq < lq) {
         const int row = q_seg0 + iq;
         char *out = (char *)b.d_q + ((int64_t)row * b.dq_stride_tok + (int64_t)h * b.dq_stride_head) * 2;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(dq[db][g4 * 4 + j] * p.softmax_scale);
-                *(bf16x4 *)(out + (db * 32 + g4 * 8 + half * 4) * 2) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(dq[j][g4 * 4 + e] * p.softmax_scale);
+                *(bf16x4 *)(out + (j * 32 + g4 * 8 + half * 4) * 2) = w;
             }
     }
 }
@@ -463,14 +424,23 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     const int64_t dkv_blocks = kv_tiles * (fused ? p.n_kv_heads : p.n_q_heads);
     const int64_t dq_blocks = q_tiles * p.n_q_heads;
     if (dkv_blocks > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const unsigned head_dkv = (unsigned)(p.n_segments * (fused ? p.n_kv_heads : p.n_q_heads));
+    const unsigned head_dq = (unsigned)(p.n_segments * p.n_q_heads);
     const ProfileHook hook = take_profile_hook();
     if (hook.start) (void)hipEventRecord(hook.start, s);
-    if (fused) mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
-    else mfma_dkv_kernel<false><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
+    if (fused) mfma_dkv_kernel<true, false><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
+    else mfma_dkv_kernel<false, false><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
     hipError_t e = hipGetLastError();
     if (hook.stop) (void)hipEventRecord(hook.stop, s);
     if (e != hipSuccess) return e;
-    mfma_dq_kernel<<<dim3((unsigned)dq_blocks), 256, 0, s>>>(b, ws.delta);
+    mfma_dq_kernel<false><<<dim3((unsigned)dq_blocks), 256, 0, s>>>(b, ws.delta);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    // the first 128 positions of every sequence, with rounding residuals (after the main dK/dV launch:
+    // in the fused mode both launches update dK/dV rows with plain read-modify-write)
+    if (fused) mfma_dkv_kernel<true, true><<<dim3(head_dkv), 256, 0, s>>>(b, ws.delta);
+    else mfma_dkv_kernel<false, true><<<dim3(head_dkv), 256, 0, s>>>(b, ws.delta);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    mfma_dq_kernel<true><<<dim3(head_dq), 256, 0, s>>>(b, ws.delta);
     return hipGetLastError();
 }
 

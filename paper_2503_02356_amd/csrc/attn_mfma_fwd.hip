@@ -2,8 +2,8 @@
 // packed sequence; a dependent chunk's queries also read the retained key/value prefix).
 //
 // One workgroup = 4 wavefronts = 128 consecutive query rows of one segment and one query head; each
-// wavefront owns 32 rows.  Key/value tiles of 64 rows are staged through LDS (double buffered) and
-// shared by the four wavefronts.  Everything is computed TRANSPOSED so that a lane owns one query:
+// wavefront owns 32 rows.  Key/value tiles of 64 rows are copied straight from global memory into LDS
+// (global_load_lds, double buffered, XOR-swizzled rows) and shared by the four wavefronts.  Everything is computed TRANSPOSED so that a lane owns one query:
 //     S^T = K Q^T   (A = K tile rows from LDS, B = Q^T kept in registers for the whole kernel)
 //     O^T += V^T P^T (A = V^T through transposing LDS reads, B = P^T straight from the S^T registers)
 // With the query on the lane axis the row maximum and row sum are in-lane reductions plus one exchange
@@ -20,42 +20,15 @@ namespace {
 constexpr int BM = 128;        // query rows per workgroup
 constexpr int BN = 64;         // key rows per tile
 constexpr int D = 128;
-constexpr int K_STRIDE = 272;  // bytes per key row in LDS: 256 + 16 so that 16 rows hit distinct 16-byte bank groups
-constexpr int V_STRIDE = 320;  // bytes per value row: 256 + 64 so that 4 rows x 64 bytes are conflict free
-constexpr int K_BYTES = BN * K_STRIDE, V_BYTES = BN * V_STRIDE;
-constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-
-struct TileLoad {
-    i32x4 k[4], v[4];
-};
-
-// Each of the 256 threads fetches 4 x 16 bytes of the K tile and of the V tile (row = idx/16, 16-byte column = idx%16).
-__device__ __forceinline__ void load_tile(TileLoad &r, const char *kbase, const char *vbase, int64_t row_bytes,
-                                          int tile_start, int last_row)
-{
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int idx = threadIdx.x + 256 * c;
-        const int row = min(tile_start + (idx >> 4), last_row);  // rows past the segment repeat its last row (masked later)
-        const int64_t off = (int64_t)row * row_bytes + (idx & 15) * 16;
-        r.k[c] = *(const i32x4 *)(kbase + off);
-        r.v[c] = *(const i32x4 *)(vbase + off);
-    }
-}
-
-__device__ __forceinline__ void store_tile(const TileLoad &r, char *stage)
-{
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        const int idx = threadIdx.x + 256 * c;
-        *(i32x4 *)(stage + (idx >> 4) * K_STRIDE + (idx & 15) * 16) = r.k[c];
-        *(i32x4 *)(stage + K_BYTES + (idx >> 4) * V_STRIDE + (idx & 15) * 16) = r.v[c];
-    }
-}
+constexpr int TILE_BYTES = BN * 256;          // one swizzled K or V tile (see mfma_common.h)
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // K then V
 
 __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
 {
-    __shared__ __attribute__((aligned(16))) char smem[2 * STAGE_BYTES];
+    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
+    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
+    __shared__ __attribute__((aligned(16))) char stage_a[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[STAGE_BYTES];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int half = lane >> 5, col = lane & 31;
 
@@ -96,6 +69,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[ks] = *(const bf16x8 *)(qrow + ks * 32 + half * 16);
     }
+    const LaneOffsets lo = lane_offsets();
 
     f32x16 o_acc[4];
 #pragma unroll
@@ -105,16 +79,17 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     float m_run = -INFINITY, l_run = 0.f;            // running max (log2 units) and this lane's partial row sum
     const float c2 = p.softmax_scale * 1.44269504088896340736f;
 
-    TileLoad regs;
-    load_tile(regs, kbase, vbase, kv_row_bytes, 0, lk - 1);
-    store_tile(regs, smem);
+    auto issue_tile = [&](int tile_start, char *stage) {
+        dma_tile<BN>(kbase + (int64_t)tile_start * kv_row_bytes, kv_row_bytes, lk - 1 - tile_start, stage);
+        dma_tile<BN>(vbase + (int64_t)tile_start * kv_row_bytes, kv_row_bytes, lk - 1 - tile_start, stage + TILE_BYTES);
+    };
+    issue_tile(0, stage_a);
+    wait_lds_dma();
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
+    auto do_tile = [&](int t, const char *stage, char *next_stage) {
         const int tile_start = t * BN;
-        char *stage = smem + (t & 1) * STAGE_BYTES;
-        const bool more = t + 1 < n_tiles;
-        if (more) load_tile(regs, kbase, vbase, kv_row_bytes, tile_start + BN, lk - 1);
+        if (t + 1 < n_tiles) issue_tile(tile_start + BN, next_stage);
 
         if (wave_active && tile_start < wave_kmax) {
             // ---- S^T = K Q^T : two 32-key blocks
@@ -123,9 +98,9 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
             for (int mb = 0; mb < 2; ++mb) {
 #pragma unroll
                 for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
-                const char *krow = stage + (mb * 32 + col) * K_STRIDE + half * 16;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) s[mb] = mfma32(lds_read_b128(krow + ks * 32), qf[ks], s[mb]);
+                for (int ks = 0; ks < 8; ++ks)
+                    s[mb] = mfma32(lds_read_b128(stage + mb * 8192 + lo.row_unit[ks]), qf[ks], s[mb]);
             }
             // ---- causal mask, only on tiles that cross this wavefront's diagonal
             if (tile_start + BN - 1 > wq0 + off) {
@@ -163,26 +138,26 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
                     for (int j = 0; j < 16; ++j) o_acc[db][j] *= alpha;
             }
             // ---- O^T += V^T P^T : contraction over the 64 keys in 4 groups of 16
-            const char *vst = stage + K_BYTES;
-            const int r16 = lane & 15;
+            const char *vst = stage + TILE_BYTES;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int tq = 0; tq < 2; ++tq) {
+                    // register 8*tq + j of block mb is key mb*32 + 16*tq + (j/4)*8 + 4*half + j%4
                     const bf16x8 pb = pack8(s[mb][8 * tq + 0], s[mb][8 * tq + 1], s[mb][8 * tq + 2], s[mb][8 * tq + 3],
                                             s[mb][8 * tq + 4], s[mb][8 * tq + 5], s[mb][8 * tq + 6], s[mb][8 * tq + 7]);
-                    // register 8*tq + j of block mb is key mb*32 + 16*tq + (j/4)*8 + 4*half + j%4
-                    const int k0 = mb * 32 + 16 * tq + half * 4;
-                    const char *va = vst + (k0 + (r16 >> 2)) * V_STRIDE + (16 * ((lane >> 4) & 1) + 4 * (r16 & 3)) * 2;
+                    const char *va = vst + mb * 8192 + tq * 4096;
 #pragma unroll
-                    for (int db = 0; db < 4; ++db) {
-                        const bf16x8 a = lds_read_tr_pair(va + db * 64, va + db * 64 + 8 * V_STRIDE);
-                        o_acc[db] = mfma32(a, pb, o_acc[db]);
-                    }
+                    for (int j = 0; j < 4; ++j)
+                        o_acc[j] = mfma32(lds_read_tr_pair(va + lo.tr_lo[j], va + lo.tr_hi[j]), pb, o_acc[j]);
                 }
         }
-        if (more) store_tile(regs, smem + ((t + 1) & 1) * STAGE_BYTES);
+        wait_lds_dma();
         __syncthreads();
+    };
+    for (int t = 0; t < n_tiles; t += 2) {
+        do_tile(t, stage_a, stage_b);
+        if (t + 1 < n_tiles) do_tile(t + 1, stage_b, stage_a);
     }
 
     if (!wave_active) return;
@@ -192,13 +167,13 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
         const int row = q_seg0 + iq;
         char *orow = (char *)p.o + ((int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head) * 2;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o_acc[db][g4 * 4 + j] * inv);
-                *(bf16x4 *)(orow + (db * 32 + g4 * 8 + half * 4) * 2) = w;
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[j][g4 * 4 + e] * inv);
+                *(bf16x4 *)(orow + (j * 32 + g4 * 8 + half * 4) * 2) = w;
             }
         if (half == 0)
             p.lse[(int64_t)h * p.n_tokens + row] = m_run * 0.69314718055994530942f + __logf(l_tot);

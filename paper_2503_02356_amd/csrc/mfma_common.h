@@ -65,6 +65,59 @@ __device__ __forceinline__ bf16x8 pack8(float a0, float a1, float a2, float a3, 
 __device__ __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 __device__ __forceinline__ int tile_off(int row, int unit) { return row * 256 + ((unit ^ swz(row)) << 4); }
 
+// Lane-constant LDS byte offsets into a swizzled tile, computed once per kernel (the XOR of the swizzle
+// cannot be folded into an instruction's immediate offset, so every distinct unit needs its own register;
+// keeping them in 16 registers beats recomputing them for each of the ~100 LDS reads per tile).
+//
+//  row_unit[ks]  operand rows read with ds_read_b128 (MFMA row/col = tile row, contraction along the tile
+//                row): offset of (row = lane % 32, logical unit 2*ks + half).  A 32-row block further down
+//                the tile adds 32*256 bytes (swz() has period 16 rows).
+//  tr_lo[db], tr_hi[db]
+//                operands read with the transposing read (contraction along the tile's ROWS, MFMA
+//                row/col = tile column 32*db + lane % 32): offsets of the two 4-row reads that make one
+//                bf16x8 operand, for contraction rows 4*half + {0..3 by lane group} and 8 rows further.
+//                32 (16) rows further down the tile add 32*256 (16*256) bytes.
+struct LaneOffsets {
+    int row_unit[8];
+    int tr_lo[4], tr_hi[4];
+};
+__device__ __forceinline__ LaneOffsets lane_offsets()
+{
+    const int lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31, r16 = lane & 15, blk = (lane >> 4) & 1;
+    LaneOffsets o;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) o.row_unit[ks] = tile_off(col, 2 * ks + half);
+    const int r_lo = 4 * half + (r16 >> 2), u0 = 2 * blk + ((r16 >> 1) & 1), sub = 8 * (r16 & 1);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        o.tr_lo[db] = tile_off(r_lo, 4 * db + u0) + sub;
+        o.tr_hi[db] = tile_off(r_lo + 8, 4 * db + u0) + sub;
+    }
+    return o;
+}
+
+// Direct global -> LDS copy of a swizzled tile of `rows` x 256 bytes by a 4-wavefront workgroup
+// (global_load_lds_dwordx4: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
+// one instruction fills 4 tile rows and the swizzle is applied on the global side: the lane that fills
+// physical unit u' of row r fetches logical unit u' ^ swz(r)).  src points at logical row 0 of the
+// tile; rows beyond last_row (relative to src) re-read last_row (the caller masks them).
+// Completion is tracked by vmcnt: wait_lds_dma() before the barrier that publishes the tile.
+template <int ROWS>
+__device__ __forceinline__ void dma_tile(const char *src, int64_t row_bytes, int last_row, char *lds_tile)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int c = 0; c < ROWS / 16; ++c) {
+        const int chunk = c * 4 + wave;                         // 4 rows = 1 KB per instruction
+        const int r = 4 * chunk + (lane >> 4);
+        const int unit = (lane & 15) ^ swz(r);
+        const char *g = src + (int64_t)min(r, last_row) * row_bytes + unit * 16;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                         (CF_LDS void *)(lds_tile + chunk * 1024), 16, 0, 0);
+    }
+}
+__device__ __forceinline__ void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
 // Finds the tile a workgroup owns.  Tiles of `tile` rows are counted per segment over cu[0..n_seg]
 // and numbered from the LAST tile of the LAST segment backwards (the later tiles of a segment see more
 // keys, so the heaviest tiles get the lowest ranks and start first).  Every lane of every wavefront
