@@ -25,6 +25,8 @@
 //              LSE and delta are one scalar per lane; dS^T feeds the last product straight from registers.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 #include "mfma_common.h"
 
@@ -40,10 +42,11 @@ constexpr float kLog2e = 1.44269504088896340736f;
 constexpr int BQ = 64;                                // query rows per tile
 constexpr int BKV = 128;                              // key rows per workgroup
 constexpr int QTILE_BYTES = BQ * 256;                 // one swizzled Q or dO tile
-constexpr int DKV_STAGE_BYTES = 2 * QTILE_BYTES + 512;  // Q, dO, LSE[64], delta[64]
-
-constexpr int TROW = 132;   // floats per row of the end-of-kernel transpose scratch (128 + 4)
-constexpr int DKV_SMEM_BYTES = 2 * DKV_STAGE_BYTES > 4 * 32 * TROW * 4 ? 2 * DKV_STAGE_BYTES : 4 * 32 * TROW * 4;
+constexpr int TROW = 132;                             // floats per row of the end-of-kernel transpose scratch (128 + 4)
+// One stage: Q tile, dO tile, LSE[64], delta[64]; rounded up so that a stage also holds the end-of-kernel
+// transpose scratch of two wavefronts (2 x 32 rows x TROW floats).
+constexpr int DKV_STAGE_BYTES = 2 * 32 * TROW * 4;
+static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
 
 // HEAD_TILES = false: the main launch.  It leaves out the tile pairs made of a sequence's first 128
 //     positions (query rows at positions < 128 x key tile 0): those rows see few keys, their P and dS are
@@ -54,9 +57,9 @@ template <bool FUSED_HEADS, bool HEAD_TILES>
 __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta)
 {
     const cf_attn_fwd_params &p = b.f;
-    // Two separate stage arrays: see the forward kernel.  The end-of-kernel transpose scratch spans both.
-    __shared__ __attribute__((aligned(16))) char smem[DKV_SMEM_BYTES];
-    char *const stage_a = smem, *const stage_b = smem + DKV_STAGE_BYTES;
+    // Two separate stage arrays (not one array with two halves): see the forward kernel.
+    __shared__ __attribute__((aligned(16))) char stage_a[DKV_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[DKV_STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
 
@@ -114,9 +117,11 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
 
     const LaneOffsets lo = lane_offsets();
 
-    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles; LSE (as
-    // log2, +inf for rows past the segment so that P = 0) and delta (0 there) go through one register of
-    // threads 0..63 / 64..127.
+    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles; LSE and delta
+    // go through one register of threads 0..63 / 64..127.  The register is only LOADED here; it is turned
+    // into its LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0 there) in
+    // publish_stats at the end of the tile, so that nothing waits for memory right after the copies start.
+    const float *stat_src = tid < 64 ? p.lse : delta;
     auto issue_tile = [&](int it, char *stage, float &stat) {
         const int h = h_first + it / n_qt;
         const int q0 = (qt_first + it % n_qt) * BQ;
@@ -125,20 +130,19 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
                      lq - 1 - q0, stage);
         dma_tile<BQ>((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2,
                      b.do_stride_tok * 2, lq - 1 - q0, stage + QTILE_BYTES);
-        if (tid < 128) {
-            const int i = q0 + (tid & 63);
-            const int64_t at = (int64_t)h * p.n_tokens + q_seg0 + min(i, lq - 1);
-            if (tid < 64) stat = i < lq ? p.lse[at] * kLog2e : INFINITY;
-            else stat = i < lq ? delta[at] : 0.f;
-        }
+        if (tid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
     };
-    auto publish_stats = [&](char *stage, float stat) {
-        if (tid < 128) ((float *)(stage + 2 * QTILE_BYTES))[tid] = stat;
+    auto publish_stats = [&](int it, char *stage, float stat) {
+        if (tid < 128) {
+            const bool live = (qt_first + it % n_qt) * BQ + (tid & 63) < lq;
+            const float v = tid < 64 ? (live ? stat * kLog2e : INFINITY) : (live ? stat : 0.f);
+            ((float *)(stage + 2 * QTILE_BYTES))[tid] = v;
+        }
     };
 
     float stat = 0.f;
     issue_tile(0, stage_a, stat);
-    publish_stats(stage_a, stat);
+    publish_stats(0, stage_a, stat);
     wait_lds_dma();
     __syncthreads();
 
@@ -151,17 +155,35 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
         if (more) issue_tile(it + 1, next_stage, stat);
 
         const bool need_mask = kt0 + BKV - 1 > q0 + off;
-        // The tile's two 32-row blocks one after the other (keeps S, dP, P, dS of only one block live).
+        // One 32-row block of the tile.  All LDS operands of a phase are fetched into registers before the
+        // phase's MFMAs start, and the transposed operands of the last two products are requested before the
+        // P/dS arithmetic so that they arrive while it runs.
+        auto block = [&](int mb, auto masked_tag) {
+            constexpr bool MASKED = decltype(masked_tag)::value;
+            bf16x8 aq[8], ado[8];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            // S = Q K_w^T and dP = dO V_w^T
+            for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) ado[ks] = lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]);
+            // S = Q K_w^T and dP = dO V_w^T (two independent accumulation chains, interleaved)
             f32x16 s, dp;
 #pragma unroll
             for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) s = mfma32(lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]), kf[ks], s);
+            for (int ks = 0; ks < 8; ++ks) {
+                s = mfma32(aq[ks], kf[ks], s);
+                dp = mfma32(ado[ks], vf[ks], dp);
+            }
+            // transposed operands: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
+            bf16x8 t_do[2][4], t_q[2][4];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) dp = mfma32(lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]), vf[ks], dp);
+            for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int ta = mb * 8192 + tq * 4096;
+                    t_do[tq][j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
+                    t_q[tq][j] = lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]);
+                }
             // P and dS: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
@@ -172,7 +194,7 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
                 for (int j = 0; j < 4; ++j) {
                     const int i = g4 * 4 + j;
                     float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[j]));
-                    if (need_mask && kv_idx > q0 + rbase + j + off) pv = 0.f;
+                    if (MASKED && kv_idx > q0 + rbase + j + off) pv = 0.f;
                     s[i] = pv;
                     dp[i] = pv * (dp[i] - d4[j]);
                 }
@@ -184,12 +206,10 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
                                         s[8 * tq + 4], s[8 * tq + 5], s[8 * tq + 6], s[8 * tq + 7]);
                 const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
                                          dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
-                // k-slot 8*half + e is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
-                const int ta = mb * 8192 + tq * 4096;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    dv[j] = mfma32(lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]), pb, dv[j]);
-                    dk[j] = mfma32(lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]), dsb, dk[j]);
+                    dv[j] = mfma32(t_do[tq][j], pb, dv[j]);
+                    dk[j] = mfma32(t_q[tq][j], dsb, dk[j]);
                 }
                 if (HEAD_TILES) {   // add the bf16 rounding residuals of P and dS
                     bf16x8 pl, dl;
@@ -200,13 +220,20 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
                     }
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        dv[j] = mfma32(lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]), pl, dv[j]);
-                        dk[j] = mfma32(lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]), dl, dk[j]);
+                        dv[j] = mfma32(t_do[tq][j], pl, dv[j]);
+                        dk[j] = mfma32(t_q[tq][j], dl, dk[j]);
                     }
                 }
             }
+        };
+        if (need_mask) {
+            block(0, std::true_type());
+            block(1, std::true_type());
+        } else {
+            block(0, std::false_type());
+            block(1, std::false_type());
         }
-        if (more) publish_stats(next_stage, stat);
+        if (more) publish_stats(it + 1, next_stage, stat);
         wait_lds_dma();
         __syncthreads();
     };
@@ -216,12 +243,12 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
     }
 
     // dK, dV: lane = key row; register group g4 of accumulator j = 4 consecutive d starting at 32*j + 8*g4 + 4*half.
-    // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB slice, free after the loop's last
-    // barrier) and then updates whole rows, 64 lanes = 64 consecutive floats: a lane-per-row update would
+    // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB half of a stage buffer, free after
+    // the loop's last barrier) and then updates whole rows, 64 lanes = 64 consecutive floats: a lane-per-row update would
     // touch 64 cache lines per instruction.
     //   FUSED_HEADS : this workgroup is the only writer of these rows in this launch: plain load, add, store.
     //   otherwise   : the query heads of a group add into the same rows: fp32 atomic adds.
-    float *tr = (float *)smem + wave * 32 * TROW;
+    float *tr = (float *)(wave < 2 ? stage_a : stage_b) + (wave & 1) * 32 * TROW;
     const int rows_valid = min(32, lk - (kt0 + 32 * wave));      // <= 0: this wavefront has no real keys
 #pragma unroll
     for (int which = 0; which < 2; ++which) {
