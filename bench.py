@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-pairs", type=float, default=6e6, help="unmasked pairs in the oracle's timed sample")
+    ap.add_argument("--cpu-pairs", type=float, default=3e7, help="unmasked pairs in the oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
@@ -122,11 +122,13 @@ def main():
     fwd_ms = np.mean([kernel_ms("fwd") for _ in range(reps)], axis=0)
     bwd_ms = np.mean([kernel_ms("bwd") for _ in range(reps)], axis=0)
     n_chunks = len(eng.chunks)
-    bwd_flop_per_launch = 10.0 * D * Hq * pairs / n_chunks          # algorithmic FLOP of an average launch
+    # The dominant kernel is the dK/dV kernel: S = QK^T, dP = dO V^T, dV += P^T dO, dK += dS^T Q, i.e. four of
+    # the backward's five contractions = 8*D FLOP per unmasked pair and query head.
+    bwd_flop_per_launch = 8.0 * D * Hq * pairs / n_chunks          # algorithmic FLOP of an average launch
     bwd_avg_ms = float(np.mean(bwd_ms))
     fwd_avg_ms = float(np.mean(fwd_ms))
     achieved = bwd_flop_per_launch / (bwd_avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "mfma_bwd_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+    roofline = {"bound": "mfma", "kernel": "mfma_dkv_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                 "traffic": MEASURED_TRAFFIC_BYTES[args.workload],
                 "avg_launch_ms": bwd_avg_ms, "launches_per_step": n_chunks,

@@ -48,24 +48,22 @@ constexpr int TROW = 132;                             // floats per row of the e
 constexpr int DKV_STAGE_BYTES = 2 * 32 * TROW * 4;
 static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
 
-// HEAD_TILES = false: the main launch.  It leaves out the tile pairs made of a sequence's first 128
+// HEAD_TILES = false: a main block.  It leaves out the tile pairs made of a sequence's first 128
 //     positions (query rows at positions < 128 x key tile 0): those rows see few keys, their P and dS are
 //     large, and the bf16 rounding of P and dS would be the largest error in dK/dV.
-// HEAD_TILES = true : a small second launch, one workgroup per (segment, head), that does exactly those
-//     tile pairs and feeds the MFMAs the bf16 values AND their bf16 rounding residuals.
-template <bool FUSED_HEADS, bool HEAD_TILES>
-__global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta)
+// HEAD_TILES = true : a head block, one per (segment, head), that does exactly those tile pairs and feeds
+//     the MFMAs the bf16 values AND their bf16 rounding residuals.  (A run-time flag, uniform over the
+//     workgroup: one code path keeps one register allocation.)
+template <bool FUSED_HEADS>
+__device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const float *__restrict__ delta, int id,
+                                         const bool HEAD_TILES, char *stage_a, char *stage_b)
 {
     const cf_attn_fwd_params &p = b.f;
-    // Two separate stage arrays (not one array with two halves): see the forward kernel.
-    __shared__ __attribute__((aligned(16))) char stage_a[DKV_STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char stage_b[DKV_STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
 
     // Block id -> (key tile rank, head); the key/value head varies fastest (XCD L2 locality, see forward).
     const int G = p.n_q_heads / p.n_kv_heads;
-    int id = blockIdx.x;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
     const int h_first = FUSED_HEADS ? kh * G : kh * G + id % G;
@@ -264,18 +262,43 @@ __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, con
         __builtin_amdgcn_wave_barrier();
         float *gbase = (which == 0 ? b.d_k : b.d_v) + (int64_t)(k_seg0 + kt0 + 32 * wave) * b.dkv_stride_tok +
                        (int64_t)kh * b.dkv_stride_head;
-        for (int r = 0; r < rows_valid; ++r) {
-            float *g = gbase + (int64_t)r * b.dkv_stride_tok;
-            if (FUSED_HEADS) {
-                g[lane] += tr[r * TROW + lane];
-                g[64 + lane] += tr[r * TROW + 64 + lane];
-            } else {
-                unsafeAtomicAdd(g + lane, tr[r * TROW + lane]);
-                unsafeAtomicAdd(g + 64 + lane, tr[r * TROW + 64 + lane]);
+        // 8 rows per step: all 16 LDS reads first, then the 16 global updates (one LDS latency per step)
+        for (int r0 = 0; r0 < rows_valid; r0 += 8) {
+            float v[16];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[2 * e] = tr[(r0 + e) * TROW + lane];
+                v[2 * e + 1] = tr[(r0 + e) * TROW + 64 + lane];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (r0 + e < rows_valid) {
+                    float *g = gbase + (int64_t)(r0 + e) * b.dkv_stride_tok;
+                    if (FUSED_HEADS) {
+                        g[lane] += v[2 * e];
+                        g[64 + lane] += v[2 * e + 1];
+                    } else {
+                        unsafeAtomicAdd(g + lane, v[2 * e]);
+                        unsafeAtomicAdd(g + 64 + lane, v[2 * e + 1]);
+                    }
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+// Blocks [0, head_blocks) do the head tiles (one per (segment, head)), the others the main work.
+template <bool FUSED_HEADS>
+__global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta,
+                                                      int head_blocks)
+{
+    // Two separate stage arrays (not one array with two halves): see the forward kernel.
+    __shared__ __attribute__((aligned(16))) char stage_a[DKV_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[DKV_STAGE_BYTES];
+    const int id = blockIdx.x;
+    const bool head = id < head_blocks;
+    dkv_body<FUSED_HEADS>(b, delta, head ? id : id - head_blocks, head, stage_a, stage_b);
 }
 
 // =====================================================================================================
@@ -286,21 +309,21 @@ constexpr int BN = 64;                       // key rows per tile
 constexpr int KVTILE_BYTES = BN * 256;       // one swizzled K or V tile
 constexpr int DQ_STAGE_BYTES = 2 * KVTILE_BYTES;
 
-// HEAD_TILES as in the dK/dV kernel: the main launch skips the 128-row tile that starts a sequence (rows at
-// positions < 128); the second launch (one workgroup per (segment, head)) does it with dS residuals.
+// HEAD_TILES as in the dK/dV kernel: the main blocks skip the 128-row tile that starts a sequence (rows at
+// positions < 128); the head blocks (one per (segment, head)) do it with dS residuals.  They also replace
+// delta of their rows: delta = <dO, O> is computed from the ROUNDED O, and for rows that see few keys
+// (large P, large |O|) that rounding would be the largest error of the whole backward pass (it lands in dK
+// of the first keys of each sequence).  The head blocks first run over their (at most 4) key tiles once to
+// form delta = sum_j P_j dP_j, which needs no O, store it for the dK/dV head blocks, then run again for dQ.
 template <bool HEAD_TILES>
-__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, const float *__restrict__ delta)
+__device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__restrict__ delta, int id,
+                                        char *stage_a, char *stage_b)
 {
     const cf_attn_fwd_params &p = b.f;
-    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
-    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
-    __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
 
     const int G = p.n_q_heads / p.n_kv_heads;
-    int id = blockIdx.x;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
     const int h = kh * G + id % G;
@@ -308,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
 
     int seg, tile_in_seg = 0;
     if (HEAD_TILES) {
-        seg = rank;                                  // grid = n_segments x heads
+        seg = rank;                                  // one block per (segment, head)
         if (seg >= p.n_segments) return;
     } else if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) {
         return;
@@ -317,7 +340,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
     const int off = lk - lq;
     const int q_tile0 = tile_in_seg * BM;
-    // the tile whose rows sit among the first 128 positions of a sequence belongs to the HEAD_TILES launch
+    // the tile whose rows sit among the first 128 positions of a sequence belongs to the head blocks
     if ((q_tile0 + off < 128) != HEAD_TILES) return;
     const int rows_valid = min(BM, lq - q_tile0);
     const int kmax = q_tile0 + rows_valid + off;     // keys [0, kmax) are visible to some row of the tile
@@ -335,6 +358,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     // Q^T and dO^T fragments (B operands): lane holds row iq, d = 16*ks + 8*half + 0..7
     bf16x8 qf[8], dof[8];
     float lse2, dlt;
+    const int64_t stat_at = (int64_t)h * p.n_tokens + q_seg0 + min(iq, lq - 1);
     {
         const int row = q_seg0 + min(iq, lq - 1);
         const char *qrow = (const char *)p.q + ((int64_t)row * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2;
@@ -344,12 +368,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
             qf[ks] = *(const bf16x8 *)(qrow + ks * 32 + half * 16);
             dof[ks] = *(const bf16x8 *)(dorow + ks * 32 + half * 16);
         }
-        lse2 = iq < lq ? p.lse[(int64_t)h * p.n_tokens + row] * kLog2e : INFINITY;   // padding rows: P = 0
-        dlt = delta[(int64_t)h * p.n_tokens + row];
+        lse2 = iq < lq ? p.lse[stat_at] * kLog2e : INFINITY;   // padding rows: P = 0
+        dlt = HEAD_TILES ? 0.f : delta[stat_at];
     }
     const float c2 = p.softmax_scale * kLog2e;
-
     const LaneOffsets lo = lane_offsets();
+
     f32x16 dq[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -361,63 +385,76 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
         dma_tile<BN>(ksrc, kv_row_bytes, lk - 1 - tile_start, stage);
         dma_tile<BN>(vsrc, kv_row_bytes, lk - 1 - tile_start, stage + KVTILE_BYTES);
     };
-    issue_tile(0, stage_a);
-    wait_lds_dma();
-    __syncthreads();
 
-    auto do_tile = [&](int t, const char *stage, char *next_stage) {
-        const int tile_start = t * BN;
-        const char *ks_ = stage;
-        const char *vs_ = stage + KVTILE_BYTES;
-        if (t + 1 < n_tiles) issue_tile(tile_start + BN, next_stage);
+    // One sweep over the key tiles.  DELTA_PASS: only accumulate sum_j P_j dP_j (this lane's keys) in dsum.
+    float dsum = 0.f;
+    auto sweep = [&](auto delta_pass_tag) {
+        constexpr bool DELTA_PASS = decltype(delta_pass_tag)::value;
+        issue_tile(0, stage_a);
+        wait_lds_dma();
+        __syncthreads();
+        auto do_tile = [&](int t, const char *stage, char *next_stage) {
+            const int tile_start = t * BN;
+            const char *ks_ = stage;
+            const char *vs_ = stage + KVTILE_BYTES;
+            if (t + 1 < n_tiles) issue_tile(tile_start + BN, next_stage);
 
-        if (wave_active && tile_start < wave_kmax) {
-            const bool need_mask = tile_start + BN - 1 > wq0 + off;
+            if (wave_active && tile_start < wave_kmax) {
+                const bool need_mask = tile_start + BN - 1 > wq0 + off;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
-                // S^T and dP^T for 32 keys: register i is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4
-                f32x16 s, dp;
+                for (int mb = 0; mb < 2; ++mb) {
+                    // S^T and dP^T for 32 keys: register i is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4
+                    f32x16 s, dp;
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
+                    for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    s = mfma32(lds_read_b128(ks_ + mb * 8192 + lo.row_unit[ks]), qf[ks], s);
+                    for (int ks = 0; ks < 8; ++ks)
+                        s = mfma32(lds_read_b128(ks_ + mb * 8192 + lo.row_unit[ks]), qf[ks], s);
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    dp = mfma32(lds_read_b128(vs_ + mb * 8192 + lo.row_unit[ks]), dof[ks], dp);
+                    for (int ks = 0; ks < 8; ++ks)
+                        dp = mfma32(lds_read_b128(vs_ + mb * 8192 + lo.row_unit[ks]), dof[ks], dp);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
-                    if (need_mask && tile_start + mb * 32 + (i >> 2) * 8 + half * 4 + (i & 3) > amax) pv = 0.f;
-                    dp[i] = pv * (dp[i] - dlt);
-                }
-                // dQ^T += K^T dS^T : contraction over these 32 keys in 2 groups of 16
+                    for (int i = 0; i < 16; ++i) {
+                        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
+                        if (need_mask && tile_start + mb * 32 + (i >> 2) * 8 + half * 4 + (i & 3) > amax) pv = 0.f;
+                        if (DELTA_PASS) dsum += pv * dp[i];
+                        else dp[i] = pv * (dp[i] - dlt);
+                    }
+                    if (DELTA_PASS) continue;
+                    // dQ^T += K^T dS^T : contraction over these 32 keys in 2 groups of 16
 #pragma unroll
-                for (int tq = 0; tq < 2; ++tq) {
-                    const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
-                                             dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
-                    const char *ka = ks_ + mb * 8192 + tq * 4096;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dsb, dq[j]);
-                    if (HEAD_TILES) {   // add the bf16 rounding residual of dS
-                        bf16x8 dl;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
+                    for (int tq = 0; tq < 2; ++tq) {
+                        const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
+                                                 dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
+                        const char *ka = ks_ + mb * 8192 + tq * 4096;
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dl, dq[j]);
+                            dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dsb, dq[j]);
+                        if (HEAD_TILES) {   // add the bf16 rounding residual of dS
+                            bf16x8 dl;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dl, dq[j]);
+                        }
                     }
                 }
             }
+            wait_lds_dma();
+            __syncthreads();
+        };
+        for (int t = 0; t < n_tiles; t += 2) {
+            do_tile(t, stage_a, stage_b);
+            if (t + 1 < n_tiles) do_tile(t + 1, stage_b, stage_a);
         }
-        wait_lds_dma();
-        __syncthreads();
     };
-    for (int t = 0; t < n_tiles; t += 2) {
-        do_tile(t, stage_a, stage_b);
-        if (t + 1 < n_tiles) do_tile(t + 1, stage_b, stage_a);
+    if (HEAD_TILES) {
+        sweep(std::true_type());
+        dlt = dsum + __shfl_xor(dsum, 32);           // the two lane halves hold different keys of the same row
+        if (wave_active && iq < lq && half == 0) delta[stat_at] = dlt;
     }
+    sweep(std::false_type());
 
     if (wave_active && iq < lq) {
         const int row = q_seg0 + iq;
@@ -434,6 +471,18 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, c
     }
 }
 
+// Blocks [0, head_blocks) do the head tiles (one per (segment, head)), the others the main work.
+__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, float *__restrict__ delta, int head_blocks)
+{
+    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
+    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
+    __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
+    const int id = blockIdx.x;
+    if (id < head_blocks) dq_body<true>(b, delta, id, stage_a, stage_b);
+    else dq_body<false>(b, delta, id - head_blocks, stage_a, stage_b);
+}
+
 }  // namespace
 
 hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStream_t s)
@@ -443,31 +492,31 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     const int64_t kv_tiles = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
     const int64_t q_tiles = (int64_t)p.n_tokens / BM + p.n_segments;
     // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
-#ifdef EXP_FORCE_FUSED
-    const bool fused = true;
-#else
     const bool fused = kv_tiles * p.n_kv_heads >= 4096;
-#endif
     const int64_t dkv_blocks = kv_tiles * (fused ? p.n_kv_heads : p.n_q_heads);
     const int64_t dq_blocks = q_tiles * p.n_q_heads;
     if (dkv_blocks > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const unsigned head_dkv = (unsigned)(p.n_segments * (fused ? p.n_kv_heads : p.n_q_heads));
-    const unsigned head_dq = (unsigned)(p.n_segments * p.n_q_heads);
+    const int head_dkv = p.n_segments * (fused ? p.n_kv_heads : p.n_q_heads);
+    const int head_dq = p.n_segments * p.n_q_heads;
+    if (dkv_blocks + head_dkv > 0x7fffffffLL || dq_blocks + head_dq > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    // dQ first: its head blocks also produce the exact delta of the head rows, which the dK/dV head blocks read.
+    mfma_dq_kernel<<<dim3((unsigned)(dq_blocks + head_dq)), 256, 0, s>>>(b, ws.delta, head_dq);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     const ProfileHook hook = take_profile_hook();
     if (hook.start) (void)hipEventRecord(hook.start, s);
-    if (fused) mfma_dkv_kernel<true, false><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
-    else mfma_dkv_kernel<false, false><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta);
-    hipError_t e = hipGetLastError();
-    if (hook.stop) (void)hipEventRecord(hook.stop, s);
-    if (e != hipSuccess) return e;
-    mfma_dq_kernel<false><<<dim3((unsigned)dq_blocks), 256, 0, s>>>(b, ws.delta);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    // the first 128 positions of every sequence, with rounding residuals (after the main dK/dV launch:
-    // in the fused mode both launches update dK/dV rows with plain read-modify-write)
-    if (fused) mfma_dkv_kernel<true, true><<<dim3(head_dkv), 256, 0, s>>>(b, ws.delta);
-    else mfma_dkv_kernel<false, true><<<dim3(head_dkv), 256, 0, s>>>(b, ws.delta);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    mfma_dq_kernel<true><<<dim3(head_dq), 256, 0, s>>>(b, ws.delta);
+    if (fused) {
+        // Fused mode updates dK/dV with plain read-modify-write: head blocks and main blocks of key tile 0 must
+        // not run concurrently, so they get launches of their own (stream order).
+        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta, 0);
+        e = hipGetLastError();
+        if (hook.stop) (void)hipEventRecord(hook.stop, s);
+        if (e != hipSuccess) return e;
+        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 256, 0, s>>>(b, ws.delta, head_dkv);
+    } else {
+        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 256, 0, s>>>(b, ws.delta, head_dkv);
+        if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    }
     return hipGetLastError();
 }
 

@@ -240,7 +240,8 @@ __global__ __launch_bounds__(256) void delta_kernel(cf_attn_bwd_params b, float 
 // that rounding would be the largest error of the whole backward pass (it lands in dK of the first keys of
 // each sequence).  Rows that see at most 64 keys therefore get delta = sum_j P_tj <dO_t, v_j> instead,
 // one key per lane, which needs no O at all.  One wavefront per (segment, one of its first 64 rows, head);
-// runs after delta_kernel and overwrites its value for those rows.
+// runs after delta_kernel and overwrites its value for those rows (scalar backward path; the MFMA path
+// does the same inside its dQ head blocks).
 template <typename T, int D>
 __global__ __launch_bounds__(kWaves * 64) void delta_head_rows_kernel(cf_attn_bwd_params b, float *delta)
 {
@@ -294,6 +295,10 @@ template <typename T, int D>
 hipError_t run_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStream_t s)
 {
     const cf_attn_fwd_params &p = b.f;
+    // exact delta for rows that see at most 64 keys (overwrites delta_kernel's value for them)
+    dim3 gh(p.n_segments * (64 / kWaves), p.n_q_heads);
+    delta_head_rows_kernel<T, D><<<gh, kWaves * 64, 0, s>>>(b, ws.delta);
+    if (hipGetLastError() != hipSuccess) return hipErrorLaunchFailure;
     dim3 gq((p.n_tokens + kWaves - 1) / kWaves, p.n_q_heads);
     const ProfileHook hook = take_profile_hook();
     if (hook.start) (void)hipEventRecord(hook.start, s);
@@ -313,10 +318,6 @@ hipError_t run_delta(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStr
 {
     const int64_t pairs = (int64_t)b.f.n_tokens * b.f.n_q_heads;
     delta_kernel<T, D><<<dim3((unsigned)((pairs + 15) / 16)), 256, 0, s>>>(b, ws.delta);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    dim3 grid(b.f.n_segments * (64 / kWaves), b.f.n_q_heads);
-    delta_head_rows_kernel<T, D><<<grid, kWaves * 64, 0, s>>>(b, ws.delta);
     return hipGetLastError();
 }
 

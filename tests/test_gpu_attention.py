@@ -105,6 +105,41 @@ def test_strided_views_and_nonzero_initial_grads():
     P.check(got, {0: dict(o=ro, lse=rlse, dq=rdq, dk=rdk, dv=rdv)}, "bf16", "strided")
 
 
+def test_long_prefix_few_queries_fused_dkv_path():
+    """A short slice (200 rows) behind a 65 400-token prefix: the dK/dV launch then has enough key tiles
+    to fuse the query heads of a group into one workgroup (plain read-modify-write, no atomics)."""
+    torch.manual_seed(1)
+    dev = "cuda:0"
+    T, P_, Hq, Hkv, D = 200, 65400, 16, 8, 128
+    q = torch.randn(T, Hq, D, device=dev).to(torch.bfloat16)
+    d_o = torch.randn(T, Hq, D, device=dev).to(torch.bfloat16)
+    k = torch.randn(P_ + T, Hkv, D, device=dev).to(torch.bfloat16)
+    v = torch.randn(P_ + T, Hkv, D, device=dev).to(torch.bfloat16)
+    cu_q, cu_k = np.array([0, T], dtype=np.int32), np.array([0, P_ + T], dtype=np.int32)
+    o = torch.empty_like(q)
+    lse = torch.empty(Hq, T, device=dev, dtype=torch.float32)
+    scale = 1 / np.sqrt(D)
+    fp = B.make_fwd_params(q, k, v, o, lse, torch.from_numpy(cu_q).to(dev), torch.from_numpy(cu_k).to(dev), scale)
+    B.cf_attn_fwd(fp)
+    dq = torch.empty_like(q)
+    dk = torch.zeros(P_ + T, Hkv, D, device=dev)
+    dv = torch.zeros_like(dk)
+    ws = torch.empty(B.cf_attn_bwd_workspace_bytes(fp), dtype=torch.uint8, device=dev)
+    bp = B.make_bwd_params(fp, d_o, dq, dk, dv, ws)
+    B.cf_attn_bwd(bp)
+    torch.cuda.synchronize()
+    f = lambda t: t.double().cpu().numpy()
+    ro, rlse = OA.chunk_attn_fwd(f(q), f(k), f(v), cu_q, cu_k, np.float32(scale))
+    rdk, rdv = np.zeros((P_ + T, Hkv, D)), np.zeros((P_ + T, Hkv, D))
+    rdq = OA.chunk_attn_bwd(f(q), f(k), f(v), ro, rlse, f(d_o), cu_q, cu_k, np.float32(scale), rdk, rdv)
+    got = {0: dict(o=f(o), lse=f(lse), dq=f(dq), dk=f(dk), dv=f(dv))}
+    print(P.check(got, {0: dict(o=ro, lse=rlse, dq=rdq, dk=rdk, dv=rdv)}, "bf16", "long prefix"))
+    dk2, dv2 = torch.zeros_like(dk), torch.zeros_like(dv)      # single writer per element: bitwise reproducible
+    B.cf_attn_bwd(B.make_bwd_params(fp, d_o, dq, dk2, dv2, ws))
+    torch.cuda.synchronize()
+    assert torch.equal(dk, dk2) and torch.equal(dv, dv2)
+
+
 def test_forward_and_dq_are_deterministic():
     """Forward and dQ have a single writer per element.  (dK/dV of short chunks sum the query heads of a
     group through fp32 atomics, so their last bits may differ between runs.)"""
