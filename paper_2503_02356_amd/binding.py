@@ -206,6 +206,9 @@ def make_fwd_params(q, k, v, o, lse, cu_q, cu_k, scale, flags=0):
     p.k, p.v, p.kv_stride_tok, p.kv_stride_head = k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1)
     p.o, p.o_stride_tok, p.o_stride_head = o.data_ptr(), o.stride(0), o.stride(1)
     p.lse = lse.data_ptr()
+    # The struct only carries raw addresses: keep the tensors alive as long as it lives, or the allocator may
+    # hand their memory (e.g. a temporary cu_seqlens tensor) to someone else before the kernels have read it.
+    p._keepalive = (q, k, v, o, lse, cu_q, cu_k)
     return p
 
 
@@ -225,6 +228,7 @@ def make_bwd_params(fwd_params, d_o, d_q, d_k, d_v, workspace):
     assert d_k.stride() == d_v.stride() and d_k.stride(2) == 1
     b.d_k, b.d_v, b.dkv_stride_tok, b.dkv_stride_head = d_k.data_ptr(), d_v.data_ptr(), d_k.stride(0), d_k.stride(1)
     b.workspace, b.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    b._keepalive = (fwd_params, d_o, d_q, d_k, d_v, workspace)      # see make_fwd_params
     return b
 
 

@@ -1,0 +1,109 @@
+"""GPU parity at the FULL sizes of configs 2 and 3, in the launch configuration bench.py times (one
+cf_attn_fwd / cf_attn_bwd call per chunk through the plan runner).  The fp64 oracle cannot redo these
+sizes whole, so it recomputes sampled outputs one by one:
+  - whole short sequences (all five tensors),
+  - single query rows of the 32768-token sequence (O, LSE, dQ; each needs only the keys before it),
+  - dK/dV of the last keys of that sequence (they only depend on the last query rows).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as OA
+from paper_2503_02356_amd import binding as B
+from paper_2503_02356_amd import inputs
+from paper_2503_02356_amd.runner import ChunkAttention
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+HQ, HKV, D = 28, 4, 128
+SCALE = np.float32(1.0 / np.sqrt(D))
+f64 = lambda t: t.detach().to(torch.float64).cpu().numpy()
+
+
+def run_full(cfg, seed):
+    def count(lens, C):
+        p = B.cf_build_chunks(lens, C)
+        n = p.n_chunks
+        p.close()
+        return n
+    lens, C = inputs.seq_lens(cfg, seed, count)
+    lens = [int(x) for x in lens]
+    plan = B.cf_build_chunks(lens, C)
+    vals = lambda sid, L: inputs.seq_values(seed, sid, lens[sid], HQ, HKV, D, "bf16")
+    eng = ChunkAttention(plan, HQ, HKV, D, "bf16").load(vals)
+    eng.zero_grads()
+    eng.run_forward()
+    eng.run_backward()
+    torch.cuda.synchronize()
+    return lens, C, plan, eng
+
+
+def check_short_sequences(lens, plan, eng, seed, picks):
+    """All five tensors of whole short sequences against unsplit oracle attention."""
+    where = {}
+    for c, ch in enumerate(eng.chunks):
+        if not ch["dependent"]:
+            for i, (sid, start, n) in enumerate(ch["segs"]):
+                where[sid] = (c, int(ch["cu_q_host"][i]), n)
+    for sid in picks:
+        c, a, n = where[sid]
+        ch = eng.chunks[c]
+        v = inputs.seq_values(seed, sid, lens[sid], HQ, HKV, D, "bf16")
+        o, lse = OA.seq_attn_fwd(v["q"], v["k"], v["v"], SCALE)
+        dq, dk, dv = OA.seq_attn_bwd(v["q"], v["k"], v["v"], o, lse, v["d_o"], SCALE)
+        got = {0: dict(o=f64(ch["o"][a:a + n]), lse=f64(ch["lse"][:, a:a + n]), dq=f64(ch["d_q"][a:a + n]),
+                       dk=f64(ch["dk"][a:a + n]), dv=f64(ch["dv"][a:a + n]))}
+        errs = P.check(got, {0: dict(o=o, lse=lse, dq=dq, dk=dk, dv=dv)}, "bf16", f"sequence {sid} (len {n})")
+        print(f"seq {sid} len {n}:", {k: f"{e[0]:.2e}/{e[1]:.2e}" for k, e in errs.items()}, flush=True)
+
+
+def test_config2_full_size_sampled_sequences():
+    lens, C, plan, eng = run_full("packed_8k", 0)
+    assert plan.n_chunks == 16 and C == 8192
+    order = np.argsort(lens)
+    picks = [int(order[0]), int(order[len(order) // 4]), int(order[len(order) // 2]), int(order[-8])]
+    check_short_sequences(lens, plan, eng, 0, picks)
+
+
+def test_config3_full_size_sampled_rows_and_tail_keys():
+    lens, C, plan, eng = run_full("long32k_mixed", 0)
+    assert plan.n_chunks == 12 and lens[0] == 32768
+    L = lens[0]
+    v = inputs.seq_values(0, 0, L, HQ, HKV, D, "bf16")
+    g = eng.chunks[0]["group"]
+    # ---- single query rows (chunk boundaries, tile edges, the very last row)
+    rows = [0, 1, 127, 8191, 8192, 8193, 16383 + 64, 24576, 24576 + 4095, L - 1]
+    got = {"o": [], "lse": [], "dq": []}
+    ref = {"o": [], "lse": [], "dq": []}
+    for r in rows:
+        c, i = r // C, r % C
+        ch = eng.chunks[c]
+        assert ch["dependent"] and ch["P"] == c * C
+        o, lse = OA.chunk_attn_fwd(v["q"][r:r + 1], v["k"][:r + 1], v["v"][:r + 1], [0, 1], [0, r + 1], SCALE)
+        dk = np.zeros((r + 1, HKV, D)); dv = np.zeros((r + 1, HKV, D))
+        dq = OA.chunk_attn_bwd(v["q"][r:r + 1], v["k"][:r + 1], v["v"][:r + 1], o, lse, v["d_o"][r:r + 1],
+                               [0, 1], [0, r + 1], SCALE, dk, dv)
+        ref["o"].append(o); ref["lse"].append(lse); ref["dq"].append(dq)
+        got["o"].append(f64(ch["o"][i:i + 1])); got["lse"].append(f64(ch["lse"][:, i:i + 1])); got["dq"].append(f64(ch["d_q"][i:i + 1]))
+    max_abs, rel = P.TOL["bf16"]
+    for name in got:
+        a, b = np.concatenate(got[name], axis=-2 if name != "lse" else -1), np.concatenate(ref[name], axis=-2 if name != "lse" else -1)
+        err, r2 = np.abs(a - b).max(), np.linalg.norm(a - b) / np.linalg.norm(b)
+        print(f"rows {name}: max-abs {err:.2e} rel-L2 {r2:.2e}", flush=True)
+        assert err <= max_abs and r2 <= rel, (name, err, r2)
+    # ---- dK/dV of the last W keys: complete once the last W query rows (all in the last chunk) are done
+    W = 160
+    qs, dos = v["q"][L - W:], v["d_o"][L - W:]
+    o, lse = OA.chunk_attn_fwd(qs, v["k"], v["v"], [0, W], [0, L], SCALE)
+    dk = np.zeros((L, HKV, D)); dv = np.zeros((L, HKV, D))
+    OA.chunk_attn_bwd(qs, v["k"], v["v"], o, lse, dos, [0, W], [0, L], SCALE, dk, dv)
+    st = eng.state[g]
+    for name, ours, theirs in (("dk", st["dk"], dk), ("dv", st["dv"], dv)):
+        a, b = f64(ours[L - W:]), theirs[L - W:]
+        err, r2 = np.abs(a - b).max(), np.linalg.norm(a - b) / np.linalg.norm(b)
+        print(f"tail keys {name}: max-abs {err:.2e} rel-L2 {r2:.2e}", flush=True)
+        assert err <= max_abs and r2 <= rel, (name, err, r2)
+    # ---- and a few of the packed short sequences of the same batch
+    order = np.argsort(lens[1:]) + 1
+    check_short_sequences(lens, plan, eng, 0, [int(order[1]), int(order[len(order) // 2])])
