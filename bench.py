@@ -95,6 +95,14 @@ def main():
         eng.run_forward()
         eng.run_backward()
 
+    # A plain streaming kernel of known size (reads 512 MiB, writes 512 MiB; larger than the 256 MiB
+    # memory-side cache): the yardstick the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the attention
+    # kernels are scaled by.  bitwise_not so that it shows up under a kernel name of its own.
+    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    torch.bitwise_not(cal_src, out=cal_dst)
+    del cal_src, cal_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
