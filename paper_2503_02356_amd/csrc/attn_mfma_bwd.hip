@@ -59,7 +59,7 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
                                          const bool HEAD_TILES, char *stage_a, char *stage_b)
 {
     const cf_attn_fwd_params &p = b.f;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
 
     // Block id -> (key tile rank, head); the key/value head varies fastest (XCD L2 locality, see forward).
@@ -120,14 +120,16 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     // into its LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0 there) in
     // publish_stats at the end of the tile, so that nothing waits for memory right after the copies start.
     const float *stat_src = tid < 64 ? p.lse : delta;
+    TileDma<BQ> dma_q, dma_do;
+    dma_q.init(p.q_stride_tok * 2);
+    dma_do.init(b.do_stride_tok * 2);
     auto issue_tile = [&](int it, char *stage, float &stat) {
         const int h = h_first + it / n_qt;
         const int q0 = (qt_first + it % n_qt) * BQ;
         const int64_t row0 = q_seg0 + q0;
-        dma_tile<BQ>((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2, p.q_stride_tok * 2,
-                     lq - 1 - q0, stage);
-        dma_tile<BQ>((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2,
-                     b.do_stride_tok * 2, lq - 1 - q0, stage + QTILE_BYTES);
+        dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
+        dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
+                     stage + QTILE_BYTES);
         if (tid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
     };
     auto publish_stats = [&](int it, char *stage, float stat) {
@@ -315,12 +317,11 @@ constexpr int DQ_STAGE_BYTES = 2 * KVTILE_BYTES;
 // (large P, large |O|) that rounding would be the largest error of the whole backward pass (it lands in dK
 // of the first keys of each sequence).  The head blocks first run over their (at most 4) key tiles once to
 // form delta = sum_j P_j dP_j, which needs no O, store it for the dK/dV head blocks, then run again for dQ.
-template <bool HEAD_TILES>
 __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__restrict__ delta, int id,
-                                        char *stage_a, char *stage_b)
+                                        const bool HEAD_TILES, char *stage_a, char *stage_b)
 {
     const cf_attn_fwd_params &p = b.f;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
 
     const int G = p.n_q_heads / p.n_kv_heads;
@@ -352,8 +353,10 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     const int amax = iq + off;                       // last visible key of this lane's row
 
     const int64_t kv_row_bytes = p.kv_stride_tok * 2;
-    const char *kbase = (const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
-    const char *vbase = (const char *)p.v + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
+    const char *kbase = uniform((const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2);
+    const char *vbase = uniform((const char *)p.v + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2);
+    TileDma<BN> dma;
+    dma.init(kv_row_bytes);
 
     // Q^T and dO^T fragments (B operands): lane holds row iq, d = 16*ks + 8*half + 0..7
     bf16x8 qf[8], dof[8];
@@ -381,9 +384,8 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
         for (int j = 0; j < 16; ++j) dq[i][j] = 0.f;
 
     auto issue_tile = [&](int tile_start, char *stage) {
-        const char *ksrc = kbase + (int64_t)tile_start * kv_row_bytes, *vsrc = vbase + (int64_t)tile_start * kv_row_bytes;
-        dma_tile<BN>(ksrc, kv_row_bytes, lk - 1 - tile_start, stage);
-        dma_tile<BN>(vsrc, kv_row_bytes, lk - 1 - tile_start, stage + KVTILE_BYTES);
+        dma.issue(kbase + (int64_t)tile_start * kv_row_bytes, lk - 1 - tile_start, stage);
+        dma.issue(vbase + (int64_t)tile_start * kv_row_bytes, lk - 1 - tile_start, stage + KVTILE_BYTES);
     };
 
     // One sweep over the key tiles.  DELTA_PASS: only accumulate sum_j P_j dP_j (this lane's keys) in dsum.
@@ -479,8 +481,8 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, f
     __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
     const int id = blockIdx.x;
-    if (id < head_blocks) dq_body<true>(b, delta, id, stage_a, stage_b);
-    else dq_body<false>(b, delta, id - head_blocks, stage_a, stage_b);
+    const bool head = id < head_blocks;   // a run-time flag, uniform over the workgroup: one code path, one register allocation
+    dq_body(b, delta, head ? id : id - head_blocks, head, stage_a, stage_b);
 }
 
 }  // namespace

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
     __shared__ __attribute__((aligned(16))) char stage_a[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) char stage_b[STAGE_BYTES];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
 
     // Block id -> (tile rank, head).  The key/value head varies fastest so that the workgroups an XCD
@@ -58,8 +58,10 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     const int amax = iq + off;                       // last visible key of this lane's row
 
     const int64_t kv_row_bytes = p.kv_stride_tok * 2;
-    const char *kbase = (const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
-    const char *vbase = (const char *)p.v + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
+    const char *kbase = uniform((const char *)p.k + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2);
+    const char *vbase = uniform((const char *)p.v + ((int64_t)k_seg0 * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2);
+    TileDma<BN> dma;
+    dma.init(kv_row_bytes);
 
     // Q^T fragments: lane (col, half) holds row iq, d = 16*ks + 8*half + 0..7.
     bf16x8 qf[8];
@@ -80,8 +82,8 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     const float c2 = p.softmax_scale * 1.44269504088896340736f;
 
     auto issue_tile = [&](int tile_start, char *stage) {
-        dma_tile<BN>(kbase + (int64_t)tile_start * kv_row_bytes, kv_row_bytes, lk - 1 - tile_start, stage);
-        dma_tile<BN>(vbase + (int64_t)tile_start * kv_row_bytes, kv_row_bytes, lk - 1 - tile_start, stage + TILE_BYTES);
+        dma.issue(kbase + (int64_t)tile_start * kv_row_bytes, lk - 1 - tile_start, stage);
+        dma.issue(vbase + (int64_t)tile_start * kv_row_bytes, lk - 1 - tile_start, stage + TILE_BYTES);
     };
     issue_tile(0, stage_a);
     wait_lds_dma();

@@ -96,26 +96,60 @@ __device__ __forceinline__ LaneOffsets lane_offsets()
     return o;
 }
 
-// Direct global -> LDS copy of a swizzled tile of `rows` x 256 bytes by a 4-wavefront workgroup
+// Index of this wavefront inside its workgroup, as a value the compiler knows to be wave-uniform.
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
+// Direct global -> LDS copy of a swizzled tile of ROWS x 256 bytes by a 4-wavefront workgroup
 // (global_load_lds_dwordx4: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
 // one instruction fills 4 tile rows and the swizzle is applied on the global side: the lane that fills
-// physical unit u' of row r fetches logical unit u' ^ swz(r)).  src points at logical row 0 of the
-// tile; rows beyond last_row (relative to src) re-read last_row (the caller masks them).
+// physical unit u' of row r fetches logical unit u' ^ swz(r)).
+// The per-lane byte offsets inside a tile are computed once (ROWS/16 registers); per tile the source is a
+// wave-uniform pointer to logical row 0, so the address arithmetic of a copy is scalar.  Rows beyond last_row
+// (relative to src) re-read last_row (the caller masks them): only the last tile of a segment takes that path.
 // Completion is tracked by vmcnt: wait_lds_dma() before the barrier that publishes the tile.
 template <int ROWS>
-__device__ __forceinline__ void dma_tile(const char *src, int64_t row_bytes, int last_row, char *lds_tile)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+struct TileDma {
+    unsigned off[ROWS / 16];      // row * row_bytes + unit * 16 for this lane's piece of copy c
+    unsigned row_bytes;
+
+    __device__ __forceinline__ void init(int64_t row_bytes_)
+    {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+        row_bytes = (unsigned)row_bytes_;
 #pragma unroll
-    for (int c = 0; c < ROWS / 16; ++c) {
-        const int chunk = c * 4 + wave;                         // 4 rows = 1 KB per instruction
-        const int r = 4 * chunk + (lane >> 4);
-        const int unit = (lane & 15) ^ swz(r);
-        const char *g = src + (int64_t)min(r, last_row) * row_bytes + unit * 16;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                         (CF_LDS void *)(lds_tile + chunk * 1024), 16, 0, 0);
+        for (int c = 0; c < ROWS / 16; ++c) {
+            const int r = 4 * (c * 4 + wave) + (lane >> 4);
+            off[c] = (unsigned)r * row_bytes + ((lane & 15) ^ swz(r)) * 16;
+        }
     }
+    __device__ __forceinline__ void issue(const char *src, int last_row, char *lds_tile) const
+    {
+        const int lane = threadIdx.x & 63, wave = wave_id();
+        if (last_row >= ROWS - 1) {
+#pragma unroll
+            for (int c = 0; c < ROWS / 16; ++c)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off[c]),
+                                                 (CF_LDS void *)(lds_tile + (c * 4 + wave) * 1024), 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int c = 0; c < ROWS / 16; ++c) {
+                const int r = 4 * (c * 4 + wave) + (lane >> 4);
+                const char *g = src + (unsigned)min(r, last_row) * row_bytes + ((lane & 15) ^ swz(r)) * 16;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                                 (CF_LDS void *)(lds_tile + (c * 4 + wave) * 1024), 16, 0, 0);
+            }
+        }
+    }
+};
+// Makes a pointer / an int that is the same in every lane known as such to the compiler.
+template <typename T>
+__device__ __forceinline__ T *uniform(T *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (T *)(((uint64_t)hi << 32) | lo);
 }
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 // Finds the tile a workgroup owns.  Tiles of `tile` rows are counted per segment over cu[0..n_seg]
@@ -141,8 +175,8 @@ __device__ __forceinline__ bool locate_tile(const int32_t *cu, int n_seg, int ti
             const int first = __ffsll((long long)ball) - 1;
             const int exc = __shfl(inc - cnt, first);
             const int c = __shfl(cnt, first);
-            seg = n_seg - 1 - (base + first);
-            tile_in_seg = c - 1 - (rank - exc);
+            seg = __builtin_amdgcn_readfirstlane(n_seg - 1 - (base + first));
+            tile_in_seg = __builtin_amdgcn_readfirstlane(c - 1 - (rank - exc));
             return true;
         }
         rank -= total;
