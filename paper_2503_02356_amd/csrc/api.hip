@@ -56,6 +56,11 @@ bool use_mfma(const cf_attn_fwd_params &p) { return mfma_shape(p) && p.softmax_s
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 int64_t delta_bytes(const cf_attn_fwd_params &p) { return round_up((int64_t)p.n_q_heads * p.n_tokens * 4, 256); }
+// counters (256 bytes) + two arrays of 16-byte items
+int64_t worklist_bytes(const cf_attn_fwd_params &p)
+{
+    return mfma_shape(p) ? 256 + 2 * cf::dkv_worklist_capacity(p) * 16 : 0;
+}
 
 int hip_fail(const char *who, hipError_t e)
 {
@@ -93,7 +98,7 @@ extern "C" int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p)
     if (int rc = check_fwd(p, "cf_attn_bwd_workspace_bytes", true)) return rc;
     if (p->flags & ~CF_FLAG_SCALAR_KERNELS)
         return cf::fail(CF_EINVAL, "cf_attn_bwd_workspace_bytes: unknown flags 0x%x", p->flags);
-    return delta_bytes(*p);
+    return delta_bytes(*p) + worklist_bytes(*p);
 }
 
 extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
@@ -115,12 +120,14 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
     if (!aligned(b->d_o, 16) || !aligned(b->d_q, 16) || !aligned(b->d_k, 16) || !aligned(b->d_v, 16) ||
         !aligned(b->workspace, 256))
         return cf::fail(CF_EINVAL, "%s: d_o, d_q, d_k, d_v must be 16-byte and workspace 256-byte aligned", who);
-    const int64_t need = delta_bytes(p);
+    const int64_t need = delta_bytes(p) + worklist_bytes(p);
     if (b->workspace_bytes < need)
         return cf::fail(CF_EINVAL, "%s: workspace has %lld bytes, %lld needed", who, (long long)b->workspace_bytes,
                         (long long)need);
     cf::BwdWorkspace ws;
     ws.delta = static_cast<float *>(b->workspace);
+    ws.worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
+    ws.worklist_items = mfma_shape(p) ? cf::dkv_worklist_capacity(p) : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     hipError_t e = cf::launch_delta(*b, ws, s);
     if (e != hipSuccess) return hip_fail(who, e);

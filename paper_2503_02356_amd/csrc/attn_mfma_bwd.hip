@@ -48,6 +48,48 @@ constexpr int TROW = 132;                             // floats per row of the e
 constexpr int DKV_STAGE_BYTES = 2 * 32 * TROW * 4;
 static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
 
+// ---- work list of the dK/dV kernel (not used in the fused mode) -------------------------------------------
+// One item = (segment, key tile, first head of the group's share, number of heads): the workgroups of one
+// key/value head.  A key tile seen by few query tiles keeps all G heads of the group in ONE item (one
+// prologue, one epilogue, one set of atomic updates instead of G); a tile seen by many query tiles is split
+// over up to G items so that no workgroup runs much longer than kSplitTarget tile iterations.  Items that come
+// out of a split go to the first array (they are the long ones and start first), the others to the second.
+// Workspace layout (ints): [0] = n_first, [1] = n_second, [64 ...] = first array, then second array; an item
+// is int4 {segment, kt0, g0, n_heads}.
+constexpr int kSplitTarget = 48;
+
+__global__ __launch_bounds__(256) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
+{
+    __shared__ int n_first, n_second;
+    if (threadIdx.x == 0) n_first = n_second = 0;
+    __syncthreads();
+    const int G = p.n_q_heads / p.n_kv_heads;
+    i32x4 *first = (i32x4 *)(wl + 64), *second = first + capacity;
+    for (int seg = threadIdx.x; seg < p.n_segments; seg += 256) {
+        const int lq = p.cu_seqlens_q[seg + 1] - p.cu_seqlens_q[seg];
+        const int lk = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
+        const int off = lk - lq;
+        const int n_head_qt = off < 128 ? min((lq + 63) / 64, (128 - off + 63) / 64) : 0;
+        for (int kt0 = 0; kt0 < lk; kt0 += 128) {
+            const int qt_first = kt0 == 0 ? n_head_qt : max(0, kt0 - off) / 64;
+            const int n_qt = (lq + 63) / 64 - qt_first;
+            if (n_qt <= 0) continue;
+            const int sp = min(G, (G * n_qt + kSplitTarget - 1) / kSplitTarget);
+            for (int s = 0; s < sp; ++s) {
+                const int g0 = s * G / sp, g1 = (s + 1) * G / sp;
+                i32x4 item = {seg, kt0, g0, g1 - g0};
+                if (sp > 1) first[atomicAdd(&n_first, 1)] = item;
+                else second[atomicAdd(&n_second, 1)] = item;
+            }
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        wl[0] = n_first;
+        wl[1] = n_second;
+    }
+}
+
 // HEAD_TILES = false: a main block.  It leaves out the tile pairs made of a sequence's first 128
 //     positions (query rows at positions < 128 x key tile 0): those rows see few keys, their P and dS are
 //     large, and the bf16 rounding of P and dS would be the largest error in dK/dV.
@@ -56,33 +98,44 @@ static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
 //     workgroup: one code path keeps one register allocation.)
 template <bool FUSED_HEADS>
 __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const float *__restrict__ delta, int id,
-                                         const bool HEAD_TILES, char *stage_a, char *stage_b)
+                                         const bool HEAD_TILES, const int *__restrict__ wl, int capacity,
+                                         char *stage_a, char *stage_b)
 {
     const cf_attn_fwd_params &p = b.f;
     const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
 
-    // Block id -> (key tile rank, head); the key/value head varies fastest (XCD L2 locality, see forward).
+    // Block id -> (item, key/value head); the key/value head varies fastest (XCD L2 locality, see forward).
+    //   fused mode : item = key tile rank, all G heads of the group
+    //   otherwise  : head blocks: item = segment, all G heads; main blocks: item = entry of the work list
     const int G = p.n_q_heads / p.n_kv_heads;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
-    const int h_first = FUSED_HEADS ? kh * G : kh * G + id % G;
-    const int n_heads = FUSED_HEADS ? G : 1;
-    const int rank = FUSED_HEADS ? id : id / G;
-
-    int seg, t_rev = 0;
+    int seg, kt0 = 0, g0 = 0, n_heads = G;
     if (HEAD_TILES) {
-        seg = rank;                                  // grid = n_segments x heads
+        seg = id;                                    // one head block per (segment, key/value head)
         if (seg >= p.n_segments) return;
-    } else if (!locate_tile(p.cu_seqlens_k, p.n_segments, BKV, rank, seg, t_rev)) {
-        return;
+    } else if (FUSED_HEADS) {
+        int t_rev;
+        if (!locate_tile(p.cu_seqlens_k, p.n_segments, BKV, id, seg, t_rev)) return;
+        // locate_tile numbers tiles from the end; the FIRST key tiles of a segment are seen by the most rows, so
+        // flip the order inside the segment to start the heaviest tiles first.
+        const int lk_ = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
+        kt0 = ((lk_ + BKV - 1) / BKV - 1 - t_rev) * BKV;
+    } else {
+        const int n_first = wl[0], n_second = wl[1];
+        if (id >= n_first + n_second) return;
+        const i32x4 *items = (const i32x4 *)(wl + 64);
+        const i32x4 item = id < n_first ? items[id] : items[capacity + id - n_first];
+        seg = uniform(item[0]);
+        kt0 = uniform(item[1]);
+        g0 = uniform(item[2]);
+        n_heads = uniform(item[3]);
     }
+    const int h_first = kh * G + g0;
     const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
     const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
     const int off = lk - lq;
-    // locate_tile numbers tiles from the end; the FIRST key tiles of a segment are seen by the most rows,
-    // so flip the order inside the segment to start the heaviest tiles first.
-    const int kt0 = HEAD_TILES ? 0 : ((lk + BKV - 1) / BKV - 1 - t_rev) * BKV;
     const int i_min = max(0, kt0 - off);             // first query row that sees any key of this tile
     // query tiles whose rows sit at positions < 128 of the sequence (only key tile 0 can see them)
     const int n_head_qt = off < 128 ? min((lq + BQ - 1) / BQ, (128 - off + BQ - 1) / BQ) : 0;
@@ -154,12 +207,10 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         const bool more = it + 1 < n_iter;
         if (more) issue_tile(it + 1, next_stage, stat);
 
-        const bool need_mask = kt0 + BKV - 1 > q0 + off;
         // One 32-row block of the tile.  All LDS operands of a phase are fetched into registers before the
         // phase's MFMAs start, and the transposed operands of the last two products are requested before the
         // P/dS arithmetic so that they arrive while it runs.
-        auto block = [&](int mb, auto masked_tag) {
-            constexpr bool MASKED = decltype(masked_tag)::value;
+        auto block = [&](int mb) {
             bf16x8 aq[8], ado[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]);
@@ -184,7 +235,11 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
                     t_do[tq][j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
                     t_q[tq][j] = lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]);
                 }
-            // P and dS: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key
+            // P and dS: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key.
+            // The causal mask is applied as a select on every block (two VALU operations per element): a branch
+            // around it would cut the block into separately scheduled pieces, and a branch around the whole
+            // block would make the accumulators meet at a join.
+            const int lim = kv_idx - off - q0 - mb * 32 - half * 4;   // masked iff lim > 8*g4 + j
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
                 const int rbase = mb * 32 + g4 * 8 + half * 4;
@@ -194,7 +249,7 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
                 for (int j = 0; j < 4; ++j) {
                     const int i = g4 * 4 + j;
                     float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[j]));
-                    if (MASKED && kv_idx > q0 + rbase + j + off) pv = 0.f;
+                    if (lim > g4 * 8 + j) pv = 0.f;
                     s[i] = pv;
                     dp[i] = pv * (dp[i] - d4[j]);
                 }
@@ -226,13 +281,8 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
                 }
             }
         };
-        if (need_mask) {
-            block(0, std::true_type());
-            block(1, std::true_type());
-        } else {
-            block(0, std::false_type());
-            block(1, std::false_type());
-        }
+        block(0);
+        block(1);
         if (more) publish_stats(it + 1, next_stage, stat);
         wait_lds_dma();
         __syncthreads();
@@ -290,17 +340,17 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     }
 }
 
-// Blocks [0, head_blocks) do the head tiles (one per (segment, head)), the others the main work.
+// Blocks [0, head_blocks) do the head tiles (one per (segment, key/value head)), the others the main work.
 template <bool FUSED_HEADS>
 __global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta,
-                                                      int head_blocks)
+                                                      int head_blocks, const int *__restrict__ wl, int capacity)
 {
     // Two separate stage arrays (not one array with two halves): see the forward kernel.
     __shared__ __attribute__((aligned(16))) char stage_a[DKV_STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) char stage_b[DKV_STAGE_BYTES];
     const int id = blockIdx.x;
     const bool head = id < head_blocks;
-    dkv_body<FUSED_HEADS>(b, delta, head ? id : id - head_blocks, head, stage_a, stage_b);
+    dkv_body<FUSED_HEADS>(b, delta, head ? id : id - head_blocks, head, wl, capacity, stage_a, stage_b);
 }
 
 // =====================================================================================================
@@ -487,6 +537,12 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, f
 
 }  // namespace
 
+int64_t dkv_worklist_capacity(const cf_attn_fwd_params &p)
+{
+    // sum over segments of ceil(Lk / 128) <= n_kv_tokens / 128 + n_segments key tiles, each split in at most G items
+    return ((int64_t)p.n_kv_tokens / BKV + p.n_segments) * (p.n_q_heads / p.n_kv_heads);
+}
+
 hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStream_t s)
 {
     const cf_attn_fwd_params &p = b.f;
@@ -495,28 +551,33 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     const int64_t q_tiles = (int64_t)p.n_tokens / BM + p.n_segments;
     // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
     const bool fused = kv_tiles * p.n_kv_heads >= 4096;
-    const int64_t dkv_blocks = kv_tiles * (fused ? p.n_kv_heads : p.n_q_heads);
     const int64_t dq_blocks = q_tiles * p.n_q_heads;
-    if (dkv_blocks > 0x7fffffffLL || dq_blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
-    const int head_dkv = p.n_segments * (fused ? p.n_kv_heads : p.n_q_heads);
     const int head_dq = p.n_segments * p.n_q_heads;
-    if (dkv_blocks + head_dkv > 0x7fffffffLL || dq_blocks + head_dq > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    const int head_dkv = p.n_segments * p.n_kv_heads;
+    const int64_t dkv_blocks = (fused ? kv_tiles : ws.worklist_items) * p.n_kv_heads;
+    if (dkv_blocks + head_dkv > 0x7fffffffLL || dq_blocks + head_dq > 0x7fffffffLL || ws.worklist_items > 0x7fffffffLL)
+        return hipErrorInvalidConfiguration;
+    hipError_t e;
+    if (!fused) {
+        dkv_worklist_kernel<<<1, 256, 0, s>>>(p, ws.worklist, (int)ws.worklist_items);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     // dQ first: its head blocks also produce the exact delta of the head rows, which the dK/dV head blocks read.
     mfma_dq_kernel<<<dim3((unsigned)(dq_blocks + head_dq)), 256, 0, s>>>(b, ws.delta, head_dq);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     const ProfileHook hook = take_profile_hook();
     if (hook.start) (void)hipEventRecord(hook.start, s);
     if (fused) {
         // Fused mode updates dK/dV with plain read-modify-write: head blocks and main blocks of key tile 0 must
         // not run concurrently, so they get launches of their own (stream order).
-        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta, 0);
+        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta, 0, nullptr, 0);
         e = hipGetLastError();
         if (hook.stop) (void)hipEventRecord(hook.stop, s);
         if (e != hipSuccess) return e;
-        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 256, 0, s>>>(b, ws.delta, head_dkv);
+        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 256, 0, s>>>(b, ws.delta, head_dkv, nullptr, 0);
     } else {
-        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 256, 0, s>>>(b, ws.delta, head_dkv);
+        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 256, 0, s>>>(b, ws.delta, head_dkv, ws.worklist,
+                                                                                     (int)ws.worklist_items);
         if (hook.stop) (void)hipEventRecord(hook.stop, s);
     }
     return hipGetLastError();

@@ -6,10 +6,17 @@
 
 namespace cf {
 
-// Backward scratch inside the caller's workspace: delta [Hq][T] fp32 = rowsum(dO * O).
+// Backward scratch inside the caller's workspace:
+//   delta     [Hq][T] fp32 = rowsum(dO * O)
+//   worklist  bf16 MFMA path only: the dK/dV kernel's work items, written by a small kernel of the same call
+//             (layout in attn_mfma_bwd.hip); worklist_items = capacity of each of its two item arrays
 struct BwdWorkspace {
     float *delta;
+    int *worklist;
+    int64_t worklist_items;
 };
+// Upper bound on the dK/dV work items of a launch (one item = a key tile and a set of query heads of one group).
+int64_t dkv_worklist_capacity(const cf_attn_fwd_params &p);
 
 // One-shot event pair recorded around the main kernel of the next launch on this thread (see
 // cf_profile_next_call); both NULL when unset.
