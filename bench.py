@@ -113,6 +113,22 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     tflops = flop_step / (ms_per_step * 1e-3) / 1e12
 
+    # ---- forward-only and backward-only passes (outside the timed steps above)
+    def wall_ms(fn, n):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / n
+
+    def bwd_pass():
+        eng.zero_grads()
+        eng.run_backward()
+    part_reps = max(1, min(args.steps, 5))
+    fwd_pass_ms = wall_ms(eng.run_forward, part_reps)
+    bwd_pass_ms = wall_ms(bwd_pass, part_reps)
+
     # ---- per-kernel durations with HIP events on the launch stream (same launches, second pass)
     def kernel_ms(kind):
         evs = []
@@ -151,6 +167,9 @@ def main():
                       "unmasked_pairs": int(pairs), "flop_per_step": flop_step, "seed": args.seed,
                       "plan_build_ms": plan_ms},
            "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
+           "fwd_only": {"ms": fwd_pass_ms, "tflops": 4.0 * D * Hq * pairs / (fwd_pass_ms * 1e-3) / 1e12},
+           "bwd_only": {"ms": bwd_pass_ms, "tflops": 10.0 * D * Hq * pairs / (bwd_pass_ms * 1e-3) / 1e12,
+                        "includes": "zeroing of the dK/dV buffers"},
            "roofline": roofline}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(lens, cfg, args.seed, args.cpu_pairs)

@@ -129,8 +129,13 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
     ws.worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
     ws.worklist_items = mfma_shape(p) ? cf::dkv_worklist_capacity(p) : 0;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = cf::launch_delta(*b, ws, s);
-    if (e != hipSuccess) return hip_fail(who, e);
-    e = use_mfma(p) ? cf::launch_mfma_bwd(*b, ws, s) : cf::launch_simple_bwd(*b, ws, s);
+    hipError_t e = hipSuccess;
+    if (use_mfma(p)) {
+        e = cf::launch_mfma_bwd(*b, ws, s);          // its dQ kernel forms delta itself
+    } else {
+        e = cf::launch_delta(*b, ws, s);
+        if (e != hipSuccess) return hip_fail(who, e);
+        e = cf::launch_simple_bwd(*b, ws, s);
+    }
     return e == hipSuccess ? CF_OK : hip_fail(who, e);
 }

@@ -58,19 +58,22 @@ static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
 // is int4 {segment, kt0, g0, n_heads}.
 constexpr int kSplitTarget = 48;
 
-__global__ __launch_bounds__(256) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
+__global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
 {
     __shared__ int n_first, n_second;
     if (threadIdx.x == 0) n_first = n_second = 0;
     __syncthreads();
     const int G = p.n_q_heads / p.n_kv_heads;
     i32x4 *first = (i32x4 *)(wl + 64), *second = first + capacity;
-    for (int seg = threadIdx.x; seg < p.n_segments; seg += 256) {
+    // Segments one after the other (their bounds are uniform loads), the key tiles of a segment in parallel.  The
+    // order inside an array follows the order in which the atomic counters are served: roughly ascending key
+    // tiles, i.e. the tiles seen by the most queries first.
+    for (int seg = 0; seg < p.n_segments; ++seg) {
         const int lq = p.cu_seqlens_q[seg + 1] - p.cu_seqlens_q[seg];
         const int lk = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
         const int off = lk - lq;
         const int n_head_qt = off < 128 ? min((lq + 63) / 64, (128 - off + 63) / 64) : 0;
-        for (int kt0 = 0; kt0 < lk; kt0 += 128) {
+        for (int kt0 = threadIdx.x * 128; kt0 < lk; kt0 += 1024 * 128) {
             const int qt_first = kt0 == 0 ? n_head_qt : max(0, kt0 - off) / 64;
             const int n_qt = (lq + 63) / 64 - qt_first;
             if (n_qt <= 0) continue;
@@ -422,7 +425,20 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
             dof[ks] = *(const bf16x8 *)(dorow + ks * 32 + half * 16);
         }
         lse2 = iq < lq ? p.lse[stat_at] * kLog2e : INFINITY;   // padding rows: P = 0
-        dlt = HEAD_TILES ? 0.f : delta[stat_at];
+        // delta = <dO, O> of this lane's row (section 4.2's backward needs it for dS): each lane half sums its 64 d.
+        // The main blocks publish it for the dK/dV kernel; the head blocks replace it below.
+        dlt = 0.f;
+        if (!HEAD_TILES) {
+            const char *orow = (const char *)p.o + ((int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head) * 2;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 of = *(const bf16x8 *)(orow + ks * 32 + half * 16);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dlt = __builtin_fmaf((float)of[e], (float)dof[ks][e], dlt);
+            }
+            dlt += __shfl_xor(dlt, 32);
+            if (iq < lq && half == 0) delta[stat_at] = dlt;
+        }
     }
     const float c2 = p.softmax_scale * kLog2e;
     const LaneOffsets lo = lane_offsets();
@@ -559,10 +575,11 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
         return hipErrorInvalidConfiguration;
     hipError_t e;
     if (!fused) {
-        dkv_worklist_kernel<<<1, 256, 0, s>>>(p, ws.worklist, (int)ws.worklist_items);
+        dkv_worklist_kernel<<<1, 1024, 0, s>>>(p, ws.worklist, (int)ws.worklist_items);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    // dQ first: its head blocks also produce the exact delta of the head rows, which the dK/dV head blocks read.
+    // dQ first: it also produces delta (main blocks: <dO, O>; head blocks: the exact sum for the head rows), which
+    // the dK/dV kernel reads.
     mfma_dq_kernel<<<dim3((unsigned)(dq_blocks + head_dq)), 256, 0, s>>>(b, ws.delta, head_dq);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const ProfileHook hook = take_profile_hook();
