@@ -179,36 +179,46 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     TileDma<BQ> dma_q, dma_do;
     dma_q.init(p.q_stride_tok * 2);
     dma_do.init(b.do_stride_tok * 2);
-    auto issue_tile = [&](int it, char *stage, float &stat) {
-        const int h = h_first + it / n_qt;
-        const int q0 = (qt_first + it % n_qt) * BQ;
+    // The tiles are visited head by head, query tiles ascending.  (nx_h, nx_qt) is the tile the next copy fetches;
+    // it advances by additions only (a division per tile would cost more than the copy instructions).
+    int nx_h = h_first, nx_qt = qt_first;
+    const int qt_end = qt_first + n_qt;
+    auto issue_tile = [&](char *stage, float &stat) {
+        const int h = nx_h, q0 = nx_qt * BQ;
         const int64_t row0 = q_seg0 + q0;
         dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
         dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
                      stage + QTILE_BYTES);
         if (tid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
+        if (++nx_qt == qt_end) {
+            nx_qt = qt_first;
+            ++nx_h;
+        }
     };
-    auto publish_stats = [&](int it, char *stage, float stat) {
+    // q0_tile: first row of the tile the stats belong to
+    auto publish_stats = [&](int q0_tile, char *stage, float stat) {
         if (tid < 128) {
-            const bool live = (qt_first + it % n_qt) * BQ + (tid & 63) < lq;
+            const bool live = q0_tile + (tid & 63) < lq;
             const float v = tid < 64 ? (live ? stat * kLog2e : INFINITY) : (live ? stat : 0.f);
             ((float *)(stage + 2 * QTILE_BYTES))[tid] = v;
         }
     };
 
     float stat = 0.f;
-    issue_tile(0, stage_a, stat);
-    publish_stats(0, stage_a, stat);
+    issue_tile(stage_a, stat);
+    publish_stats(qt_first * BQ, stage_a, stat);
     wait_lds_dma();
     __syncthreads();
+    int cur_qt = qt_first;                           // query tile of the iteration in flight
 
     auto do_tile = [&](int it, const char *qs, char *next_stage) {
-        const int q0 = (qt_first + it % n_qt) * BQ;
+        const int q0 = cur_qt * BQ;
+        if (++cur_qt == qt_end) cur_qt = qt_first;
         const char *dos = qs + QTILE_BYTES;
         const float *lse_s = (const float *)(qs + 2 * QTILE_BYTES);
         const float *del_s = lse_s + 64;
         const bool more = it + 1 < n_iter;
-        if (more) issue_tile(it + 1, next_stage, stat);
+        if (more) issue_tile(next_stage, stat);
 
         // One 32-row block of the tile.  All LDS operands of a phase are fetched into registers before the
         // phase's MFMAs start, and the transposed operands of the last two products are requested before the
@@ -286,7 +296,7 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         };
         block(0);
         block(1);
-        if (more) publish_stats(it + 1, next_stage, stat);
+        if (more) publish_stats(cur_qt * BQ, next_stage, stat);
         wait_lds_dma();
         __syncthreads();
     };

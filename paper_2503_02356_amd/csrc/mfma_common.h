@@ -103,42 +103,34 @@ __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane
 // (global_load_lds_dwordx4: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
 // one instruction fills 4 tile rows and the swizzle is applied on the global side: the lane that fills
 // physical unit u' of row r fetches logical unit u' ^ swz(r)).
-// The per-lane byte offsets inside a tile are computed once (ROWS/16 registers); per tile the source is a
-// wave-uniform pointer to logical row 0, so the address arithmetic of a copy is scalar.  Rows beyond last_row
-// (relative to src) re-read last_row (the caller masks them): only the last tile of a segment takes that path.
+// A tile takes ROWS/16 instructions per wavefront (PARTS); each costs the issuing wavefront some 30-45 clocks
+// wherever it is placed (measured), so they are simply issued together at the start of a tile.
+// Per tile the source is a wave-uniform pointer to logical row 0 (scalar address arithmetic); rows beyond
+// last_row (relative to src) re-read last_row (the caller masks them).
 // Completion is tracked by vmcnt: wait_lds_dma() before the barrier that publishes the tile.
 template <int ROWS>
 struct TileDma {
-    unsigned off[ROWS / 16];      // row * row_bytes + unit * 16 for this lane's piece of copy c
-    unsigned row_bytes;
+    static constexpr int PARTS = ROWS / 16;
+    unsigned row_bytes, unit16;   // unit16: byte offset of this lane's 16-byte unit inside its row (same for all parts)
+    int r0;                       // this lane's row in part 0; part c adds 16 rows
 
     __device__ __forceinline__ void init(int64_t row_bytes_)
     {
-        const int lane = threadIdx.x & 63, wave = wave_id();
+        const int lane = threadIdx.x & 63;
         row_bytes = (unsigned)row_bytes_;
-#pragma unroll
-        for (int c = 0; c < ROWS / 16; ++c) {
-            const int r = 4 * (c * 4 + wave) + (lane >> 4);
-            off[c] = (unsigned)r * row_bytes + ((lane & 15) ^ swz(r)) * 16;
-        }
+        r0 = 4 * wave_id() + (lane >> 4);
+        unit16 = ((lane & 15) ^ swz(r0)) * 16;       // swz() has period 16 rows
+    }
+    __device__ __forceinline__ void issue_part(const char *src, int last_row, char *lds_tile, int c) const
+    {
+        const char *g = src + ((unsigned)min(r0 + 16 * c, last_row) * row_bytes + unit16);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
+                                         (CF_LDS void *)(lds_tile + (c * 4 + wave_id()) * 1024), 16, 0, 0);
     }
     __device__ __forceinline__ void issue(const char *src, int last_row, char *lds_tile) const
     {
-        const int lane = threadIdx.x & 63, wave = wave_id();
-        if (last_row >= ROWS - 1) {
 #pragma unroll
-            for (int c = 0; c < ROWS / 16; ++c)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + off[c]),
-                                                 (CF_LDS void *)(lds_tile + (c * 4 + wave) * 1024), 16, 0, 0);
-        } else {
-#pragma unroll
-            for (int c = 0; c < ROWS / 16; ++c) {
-                const int r = 4 * (c * 4 + wave) + (lane >> 4);
-                const char *g = src + (unsigned)min(r, last_row) * row_bytes + ((lane & 15) ^ swz(r)) * 16;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                                 (CF_LDS void *)(lds_tile + (c * 4 + wave) * 1024), 16, 0, 0);
-            }
-        }
+        for (int c = 0; c < PARTS; ++c) issue_part(src, last_row, lds_tile, c);
     }
 };
 // Makes a pointer / an int that is the same in every lane known as such to the compiler.
