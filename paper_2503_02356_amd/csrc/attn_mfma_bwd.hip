@@ -39,14 +39,18 @@ constexpr float kLog2e = 1.44269504088896340736f;
 // =====================================================================================================
 // dK / dV
 // =====================================================================================================
-constexpr int BQ = 64;                                // query rows per tile
+constexpr int BQ = 64;                                // query rows per tile (two 32-row blocks)
 constexpr int BKV = 128;                              // key rows per workgroup
+constexpr int DKV_WAVES = 8;                          // 4 pairs: (S, P, dV) wavefront + (dP, dS, dK) wavefront
 constexpr int QTILE_BYTES = BQ * 256;                 // one swizzled Q or dO tile
 constexpr int TROW = 132;                             // floats per row of the end-of-kernel transpose scratch (128 + 4)
 // One stage: Q tile, dO tile, LSE[64], delta[64]; rounded up so that a stage also holds the end-of-kernel
-// transpose scratch of two wavefronts (2 x 32 rows x TROW floats).
+// transpose scratch of two wavefronts (2 x 32 rows x TROW floats).  The P exchange area has the same size:
+// 4 pairs x 2 slots x 4 KB, and the scratch of the last two wavefronts.
 constexpr int DKV_STAGE_BYTES = 2 * 32 * TROW * 4;
+constexpr int EXCH_SLOT_BYTES = 32 * 32 * 4;          // one 32 x 32 fp32 block of P
 static_assert(DKV_STAGE_BYTES >= 2 * QTILE_BYTES + 512, "stage too small");
+static_assert(DKV_STAGE_BYTES >= 4 * 2 * EXCH_SLOT_BYTES, "exchange area too small");
 
 // ---- work list of the dK/dV kernel (not used in the fused mode) -------------------------------------------
 // One item = (segment, key tile, first head of the group's share, number of heads): the workgroups of one
@@ -96,17 +100,26 @@ __global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p
 // HEAD_TILES = false: a main block.  It leaves out the tile pairs made of a sequence's first 128
 //     positions (query rows at positions < 128 x key tile 0): those rows see few keys, their P and dS are
 //     large, and the bf16 rounding of P and dS would be the largest error in dK/dV.
-// HEAD_TILES = true : a head block, one per (segment, head), that does exactly those tile pairs and feeds
-//     the MFMAs the bf16 values AND their bf16 rounding residuals.  (A run-time flag, uniform over the
+// HEAD_TILES = true : a head block, one per (segment, key/value head), that does exactly those tile pairs and
+//     feeds the MFMAs the bf16 values AND their bf16 rounding residuals.  (A run-time flag, uniform over the
 //     workgroup: one code path keeps one register allocation.)
+//
+// Eight wavefronts, two per SIMD.  Wavefronts w and w + 4 own the same 32 keys and split the work per 32-row
+// block of queries so that each keeps only ONE accumulator (64 registers) and one operand fragment:
+//     role 0 (w < 4)  : S = Q K_w^T,  P = exp2(S c - LSE)  -> fp32 P into an LDS slot,   dV_w^T += dO^T P
+//     role 1 (w >= 4) : dP = dO V_w^T,  dS = P (dP - delta) with P read from the slot,    dK_w^T += Q^T dS
+// Role 1 runs one block behind role 0 (a workgroup barrier per block), so on every SIMD one wavefront is
+// multiplying while the other does the exp / dS arithmetic.  Q/dO tiles rotate through three LDS stages: the
+// copy of tile t + 2 starts when role 1 has left tile t - 1 and has two block steps to land.
 template <bool FUSED_HEADS>
 __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const float *__restrict__ delta, int id,
-                                         const bool HEAD_TILES, const int *__restrict__ wl, int capacity,
-                                         char *stage_a, char *stage_b)
+                                         const bool HEAD_TILES, const int *__restrict__ wl, int capacity, char *st0,
+                                         char *st1, char *st2, char *exch_all)
 {
     const cf_attn_fwd_params &p = b.f;
     const int tid = threadIdx.x, lane = tid & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
+    const int role = wave >> 2, pw = wave & 3;       // role (uniform per wavefront), index of the 32-key slice
 
     // Block id -> (item, key/value head); the key/value head varies fastest (XCD L2 locality, see forward).
     //   fused mode : item = key tile rank, all G heads of the group
@@ -135,6 +148,10 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         g0 = uniform(item[2]);
         n_heads = uniform(item[3]);
     }
+    // (seg, kt0 are the same in every lane, but values that leave locate_tile's search loop do not look that way to
+    // the compiler: say so, or everything derived from them lives in vector registers.)
+    seg = uniform(seg);
+    kt0 = uniform(kt0);
     const int h_first = kh * G + g0;
     const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
     const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
@@ -145,225 +162,274 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     const int qt_first = HEAD_TILES ? 0 : (kt0 == 0 ? n_head_qt : i_min / BQ);
     const int n_qt = HEAD_TILES ? n_head_qt : (lq + BQ - 1) / BQ - qt_first;
     if (n_qt <= 0) return;                           // whole workgroup leaves before any barrier
-    const int n_iter = n_heads * n_qt;
+    const int n_tiles = n_heads * n_qt;              // (head, query tile) pairs, head by head
+    const int n_blk = 2 * n_tiles;                   // 32-row blocks; step k: role 0 does block k, role 1 block k - 1
+    const int qt_end = qt_first + n_qt;
 
-    const int kv_idx = kt0 + 32 * wave + col;        // this lane's key (segment-local)
+    const int kv_idx = kt0 + 32 * pw + col;          // this lane's key (segment-local)
     const float c2 = p.softmax_scale * kLog2e;
 
-    // K_w and V_w operand fragments (B operands of S and dP): lane = key row, 8 consecutive d per step
-    bf16x8 kf[8], vf[8];
+    // Operand fragment kept for the whole kernel (B operand of S resp. dP): K_w for role 0, V_w for role 1;
+    // lane = key row, 8 consecutive d per step.
+    bf16x8 wf[8];
     {
         const int64_t row = k_seg0 + min(kv_idx, lk - 1);
-        const char *kr = (const char *)p.k + (row * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
-        const char *vr = (const char *)p.v + (row * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
+        const char *src = (const char *)(role ? p.v : p.k) + (row * p.kv_stride_tok + (int64_t)kh * p.kv_stride_head) * 2;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            kf[ks] = *(const bf16x8 *)(kr + ks * 32 + half * 16);
-            vf[ks] = *(const bf16x8 *)(vr + ks * 32 + half * 16);
-        }
+        for (int ks = 0; ks < 8; ++ks) wf[ks] = *(const bf16x8 *)(src + ks * 32 + half * 16);
     }
-
-    f32x16 dk[4], dv[4];
+    f32x16 acc[4];                                   // role 0: dV_w^T, role 1: dK_w^T
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 16; ++j) dk[i][j] = dv[i][j] = 0.f;
-
+        for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
     const LaneOffsets lo = lane_offsets();
+    char *exch = exch_all + pw * 2 * EXCH_SLOT_BYTES + lane * 16;   // this lane's 16 bytes of row group 0, slot 0
 
-    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles; LSE and delta
-    // go through one register of threads 0..63 / 64..127.  The register is only LOADED here; it is turned
-    // into its LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0 there) in
-    // publish_stats at the end of the tile, so that nothing waits for memory right after the copies start.
+    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles (all 8 wavefronts
+    // issue their share); LSE and delta go through one register of threads 0..63 / 64..127, loaded when the copy
+    // starts and turned into their LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0
+    // there) one step later, so that nothing waits for memory right after the copies start.
     const float *stat_src = tid < 64 ? p.lse : delta;
-    TileDma<BQ> dma_q, dma_do;
+    TileDma<BQ, DKV_WAVES> dma_q, dma_do;
     dma_q.init(p.q_stride_tok * 2);
     dma_do.init(b.do_stride_tok * 2);
-    // The tiles are visited head by head, query tiles ascending.  (nx_h, nx_qt) is the tile the next copy fetches;
-    // it advances by additions only (a division per tile would cost more than the copy instructions).
-    int nx_h = h_first, nx_qt = qt_first;
-    const int qt_end = qt_first + n_qt;
-    auto issue_tile = [&](char *stage, float &stat) {
+    int nx_h = h_first, nx_qt = qt_first;            // the tile the next copy fetches (advances by additions only)
+    int stat_q0 = 0;                                 // first row of the tile the pending stat register belongs to
+    float stat = 0.f;
+    auto issue_tile = [&](char *stage) {
         const int h = nx_h, q0 = nx_qt * BQ;
         const int64_t row0 = q_seg0 + q0;
         dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
         dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
                      stage + QTILE_BYTES);
         if (tid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
+        stat_q0 = q0;
         if (++nx_qt == qt_end) {
             nx_qt = qt_first;
             ++nx_h;
         }
     };
-    // q0_tile: first row of the tile the stats belong to
-    auto publish_stats = [&](int q0_tile, char *stage, float stat) {
+    auto publish_stats = [&](char *stage) {
         if (tid < 128) {
-            const bool live = q0_tile + (tid & 63) < lq;
+            const bool live = stat_q0 + (tid & 63) < lq;
             const float v = tid < 64 ? (live ? stat * kLog2e : INFINITY) : (live ? stat : 0.f);
             ((float *)(stage + 2 * QTILE_BYTES))[tid] = v;
         }
     };
 
-    float stat = 0.f;
-    issue_tile(stage_a, stat);
-    publish_stats(qt_first * BQ, stage_a, stat);
+    issue_tile(st0);
+    publish_stats(st0);
+    if (n_tiles > 1) {
+        issue_tile(st1);
+        publish_stats(st1);
+    }
     wait_lds_dma();
     __syncthreads();
-    int cur_qt = qt_first;                           // query tile of the iteration in flight
 
-    auto do_tile = [&](int it, const char *qs, char *next_stage) {
-        const int q0 = cur_qt * BQ;
-        if (++cur_qt == qt_end) cur_qt = qt_first;
-        const char *dos = qs + QTILE_BYTES;
-        const float *lse_s = (const float *)(qs + 2 * QTILE_BYTES);
-        const float *del_s = lse_s + 64;
-        const bool more = it + 1 < n_iter;
-        if (more) issue_tile(next_stage, stat);
+    int cur_qt = qt_first;                           // query tile of the block this wavefront works on
 
-        // One 32-row block of the tile.  All LDS operands of a phase are fetched into registers before the
-        // phase's MFMAs start, and the transposed operands of the last two products are requested before the
-        // P/dS arithmetic so that they arrive while it runs.
-        auto block = [&](int mb) {
-            bf16x8 aq[8], ado[8];
+    // role 0, block kb of the tile in `stage`: S, P (to the exchange slot), dV
+    auto block_p_dv = [&](int kb, const char *stage, char *slot) {
+        const int mb = kb & 1, q0 = cur_qt * BQ;
+        const char *qs = stage, *dos = stage + QTILE_BYTES;
+        const float *lse_s = (const float *)(stage + 2 * QTILE_BYTES);
+        bf16x8 aq[8];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]);
+        for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]);
+        f32x16 s;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) ado[ks] = lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]);
-            // S = Q K_w^T and dP = dO V_w^T (two independent accumulation chains, interleaved)
-            f32x16 s, dp;
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
+        for (int ks = 0; ks < 8; ++ks) s = mfma32(aq[ks], wf[ks], s);
+        // P: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key.  The causal
+        // mask is a select on every block (no branch around arithmetic that feeds the MFMAs).
+        const int lim = kv_idx - off - q0 - mb * 32 - half * 4;   // masked iff lim > 8*g4 + j
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                s = mfma32(aq[ks], kf[ks], s);
-                dp = mfma32(ado[ks], vf[ks], dp);
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const f32x4 l4 = *(const f32x4 *)(lse_s + mb * 32 + g4 * 8 + half * 4);
+            f32x4 pw4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[g4 * 4 + j], c2, -l4[j]));
+                if (lim > g4 * 8 + j) pv = 0.f;
+                s[g4 * 4 + j] = pv;
+                pw4[j] = pv;
             }
+            *(f32x4 *)(slot + g4 * 1024) = pw4;      // lane-private position: role 1 reads it back at the same place
+        }
+        // dV_w^T += dO^T P : contraction over these 32 query rows in 2 groups of 16
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq) {
             // transposed operands: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
-            bf16x8 t_do[2][4], t_q[2][4];
+            bf16x8 t_do[4];
 #pragma unroll
-            for (int tq = 0; tq < 2; ++tq)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int ta = mb * 8192 + tq * 4096;
-                    t_do[tq][j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
-                    t_q[tq][j] = lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]);
-                }
-            // P and dS: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key.
-            // The causal mask is applied as a select on every block (two VALU operations per element): a branch
-            // around it would cut the block into separately scheduled pieces, and a branch around the whole
-            // block would make the accumulators meet at a join.
-            const int lim = kv_idx - off - q0 - mb * 32 - half * 4;   // masked iff lim > 8*g4 + j
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                const int rbase = mb * 32 + g4 * 8 + half * 4;
-                const f32x4 l4 = *(const f32x4 *)(lse_s + rbase);
-                const f32x4 d4 = *(const f32x4 *)(del_s + rbase);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int i = g4 * 4 + j;
-                    float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -l4[j]));
-                    if (lim > g4 * 8 + j) pv = 0.f;
-                    s[i] = pv;
-                    dp[i] = pv * (dp[i] - d4[j]);
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int ta = mb * 8192 + tq * 4096;
+                t_do[j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
             }
-            // dV_w^T += dO^T P and dK_w^T += Q^T dS : contraction over these 32 query rows in 2 groups of 16
+            const bf16x8 pb = pack8(s[8 * tq + 0], s[8 * tq + 1], s[8 * tq + 2], s[8 * tq + 3], s[8 * tq + 4],
+                                    s[8 * tq + 5], s[8 * tq + 6], s[8 * tq + 7]);
 #pragma unroll
-            for (int tq = 0; tq < 2; ++tq) {
-                const bf16x8 pb = pack8(s[8 * tq + 0], s[8 * tq + 1], s[8 * tq + 2], s[8 * tq + 3],
-                                        s[8 * tq + 4], s[8 * tq + 5], s[8 * tq + 6], s[8 * tq + 7]);
-                const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
-                                         dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
+            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[j], pb, acc[j]);
+            if (HEAD_TILES) {   // add the bf16 rounding residual of P
+                bf16x8 pl;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    dv[j] = mfma32(t_do[tq][j], pb, dv[j]);
-                    dk[j] = mfma32(t_q[tq][j], dsb, dk[j]);
-                }
-                if (HEAD_TILES) {   // add the bf16 rounding residuals of P and dS
-                    bf16x8 pl, dl;
+                for (int e = 0; e < 8; ++e) pl[e] = (__bf16)(s[8 * tq + e] - (float)pb[e]);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        pl[e] = (__bf16)(s[8 * tq + e] - (float)pb[e]);
-                        dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
-                    }
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        dv[j] = mfma32(t_do[tq][j], pl, dv[j]);
-                        dk[j] = mfma32(t_q[tq][j], dl, dk[j]);
-                    }
-                }
+                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[j], pl, acc[j]);
             }
-        };
-        block(0);
-        block(1);
-        if (more) publish_stats(cur_qt * BQ, next_stage, stat);
-        wait_lds_dma();
-        __syncthreads();
+        }
+        if (mb && ++cur_qt == qt_end) cur_qt = qt_first;
     };
-    for (int it = 0; it < n_iter; it += 2) {
-        do_tile(it, stage_a, stage_b);
-        if (it + 1 < n_iter) do_tile(it + 1, stage_b, stage_a);
-    }
+    // role 1 works on two blocks per step, ordered so that its phases fall into the gaps of role 0's (which runs
+    // S-MFMAs, P arithmetic, dV-MFMAs in that order): first the dS arithmetic of block k - 1 (while role 0 multiplies),
+    // then the dK MFMAs of block k - 1 and the dP MFMAs of block k (while role 0 does its arithmetic).  dP of block k
+    // stays in registers until the next step.
+    f32x16 dp;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) dp[j] = 0.f;
+    auto finish_ds_dk = [&](int kb, const char *stage, const char *slot) {
+        const int mb = kb & 1;
+        const char *qs = stage;
+        const float *del_s = (const float *)(stage + 2 * QTILE_BYTES) + 64;
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            const f32x4 d4 = *(const f32x4 *)(del_s + mb * 32 + g4 * 8 + half * 4);
+            const f32x4 p4 = *(const f32x4 *)(slot + g4 * 1024);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dp[g4 * 4 + j] = p4[j] * (dp[g4 * 4 + j] - d4[j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // dK_w^T += Q^T dS : contraction over these 32 query rows in 2 groups of 16
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq) {
+            // transposed operands: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
+            bf16x8 t_q[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ta = mb * 8192 + tq * 4096;
+                t_q[j] = lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]);
+            }
+            const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3], dp[8 * tq + 4],
+                                     dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[j], dsb, acc[j]);
+            if (HEAD_TILES) {   // add the bf16 rounding residual of dS
+                bf16x8 dl;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[j], dl, acc[j]);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto start_dp = [&](int kb, const char *stage) {
+        const int mb = kb & 1;
+        const char *dos = stage + QTILE_BYTES;
+        bf16x8 ado[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) ado[ks] = lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) dp[j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) dp = mfma32(ado[ks], wf[ks], dp);
+    };
+
+    // Step k of n_blk + 1.  s_cur: stage of tile k/2 (role 0's block), s_prev: stage of tile (k-1)/2 (role 1's older
+    // block), s_next: stage the copy started in this step (odd k: tile (k+3)/2) lands in.  The two roles run two
+    // separate copies of the loop (same number of barriers): a value that only one role keeps across steps must not
+    // occupy registers in the other.
+    auto run = [&](auto role_tag) {
+        constexpr int ROLE = decltype(role_tag)::value;
+        auto step = [&](int k, const char *s_cur, const char *s_prev, char *s_next) {
+            const bool odd = k & 1;
+            if (odd && (k + 3) / 2 < n_tiles) issue_tile(s_next);
+            if (ROLE == 0) {
+                if (k < n_blk) block_p_dv(k, s_cur, exch + (k & 1) * EXCH_SLOT_BYTES);
+            } else {
+                if (k >= 1) finish_ds_dk(k - 1, s_prev, exch + ((k - 1) & 1) * EXCH_SLOT_BYTES);
+                if (k < n_blk) start_dp(k, s_cur);
+            }
+            if (!odd) {                              // the copy started one step ago has had a full step to land
+                if (k >= 2 && (k + 2) / 2 < n_tiles) publish_stats(const_cast<char *>(s_cur == st0 ? st1 : s_cur == st1 ? st2 : st0));
+                wait_lds_dma();
+            }
+            __syncthreads();
+        };
+        // Six steps = three tiles per trip, so that every stage is a compile-time array in every position.
+        for (int k = 0; k <= n_blk; k += 6) {
+            step(k, st0, st2, nullptr);
+            if (k + 1 <= n_blk) step(k + 1, st0, st0, st2);
+            if (k + 2 <= n_blk) step(k + 2, st1, st0, nullptr);
+            if (k + 3 <= n_blk) step(k + 3, st1, st1, st0);
+            if (k + 4 <= n_blk) step(k + 4, st2, st1, nullptr);
+            if (k + 5 <= n_blk) step(k + 5, st2, st2, st1);
+        }
+    };
+    if (role == 0) run(std::integral_constant<int, 0>());
+    else run(std::integral_constant<int, 1>());
 
     // dK, dV: lane = key row; register group g4 of accumulator j = 4 consecutive d starting at 32*j + 8*g4 + 4*half.
-    // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB half of a stage buffer, free after
-    // the loop's last barrier) and then updates whole rows, 64 lanes = 64 consecutive floats: a lane-per-row update would
-    // touch 64 cache lines per instruction.
+    // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB half of a stage / of the exchange area,
+    // all free after the loop's last barrier) and then updates whole rows, 64 lanes = 64 consecutive floats: a
+    // lane-per-row update would touch 64 cache lines per instruction.
     //   FUSED_HEADS : this workgroup is the only writer of these rows in this launch: plain load, add, store.
     //   otherwise   : the query heads of a group add into the same rows: fp32 atomic adds.
-    float *tr = (float *)(wave < 2 ? stage_a : stage_b) + (wave & 1) * 32 * TROW;
-    const int rows_valid = min(32, lk - (kt0 + 32 * wave));      // <= 0: this wavefront has no real keys
+    char *area = wave < 2 ? st0 : wave < 4 ? st1 : wave < 6 ? st2 : exch_all;
+    float *tr = (float *)area + (wave & 1) * 32 * TROW;
+    const int rows_valid = min(32, lk - (kt0 + 32 * pw));        // <= 0: this wavefront has no real keys
+    const float out_scale = role ? p.softmax_scale : 1.f;
 #pragma unroll
-    for (int which = 0; which < 2; ++which) {
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int g4 = 0; g4 < 4; ++g4) {
+            f32x4 a;
 #pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                f32x4 a;
+            for (int e = 0; e < 4; ++e) a[e] = acc[j][g4 * 4 + e] * out_scale;
+            *(f32x4 *)(tr + col * TROW + j * 32 + g4 * 8 + half * 4) = a;
+        }
+    __builtin_amdgcn_wave_barrier();
+    float *gbase = (role ? b.d_k : b.d_v) + (int64_t)(k_seg0 + kt0 + 32 * pw) * b.dkv_stride_tok + (int64_t)kh * b.dkv_stride_head;
+    // 8 rows per step: all 16 LDS reads first, then the 16 global updates (one LDS latency per step)
+    for (int r0 = 0; r0 < rows_valid; r0 += 8) {
+        float v[16];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[e] = which == 0 ? dk[j][g4 * 4 + e] * p.softmax_scale : dv[j][g4 * 4 + e];
-                *(f32x4 *)(tr + col * TROW + j * 32 + g4 * 8 + half * 4) = a;
-            }
-        __builtin_amdgcn_wave_barrier();
-        float *gbase = (which == 0 ? b.d_k : b.d_v) + (int64_t)(k_seg0 + kt0 + 32 * wave) * b.dkv_stride_tok +
-                       (int64_t)kh * b.dkv_stride_head;
-        // 8 rows per step: all 16 LDS reads first, then the 16 global updates (one LDS latency per step)
-        for (int r0 = 0; r0 < rows_valid; r0 += 8) {
-            float v[16];
+        for (int e = 0; e < 8; ++e) {
+            v[2 * e] = tr[(r0 + e) * TROW + lane];
+            v[2 * e + 1] = tr[(r0 + e) * TROW + 64 + lane];
+        }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                v[2 * e] = tr[(r0 + e) * TROW + lane];
-                v[2 * e + 1] = tr[(r0 + e) * TROW + 64 + lane];
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                if (r0 + e < rows_valid) {
-                    float *g = gbase + (int64_t)(r0 + e) * b.dkv_stride_tok;
-                    if (FUSED_HEADS) {
-                        g[lane] += v[2 * e];
-                        g[64 + lane] += v[2 * e + 1];
-                    } else {
-                        unsafeAtomicAdd(g + lane, v[2 * e]);
-                        unsafeAtomicAdd(g + 64 + lane, v[2 * e + 1]);
-                    }
+        for (int e = 0; e < 8; ++e) {
+            if (r0 + e < rows_valid) {
+                float *g = gbase + (int64_t)(r0 + e) * b.dkv_stride_tok;
+                if (FUSED_HEADS) {
+                    g[lane] += v[2 * e];
+                    g[64 + lane] += v[2 * e + 1];
+                } else {
+                    unsafeAtomicAdd(g + lane, v[2 * e]);
+                    unsafeAtomicAdd(g + 64 + lane, v[2 * e + 1]);
                 }
             }
         }
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
 // Blocks [0, head_blocks) do the head tiles (one per (segment, key/value head)), the others the main work.
 template <bool FUSED_HEADS>
-__global__ __launch_bounds__(256) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta,
-                                                      int head_blocks, const int *__restrict__ wl, int capacity)
+__global__ __launch_bounds__(64 * DKV_WAVES) void mfma_dkv_kernel(cf_attn_bwd_params b, const float *__restrict__ delta,
+                                                                 int head_blocks, const int *__restrict__ wl, int capacity)
 {
-    // Two separate stage arrays (not one array with two halves): see the forward kernel.
-    __shared__ __attribute__((aligned(16))) char stage_a[DKV_STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char stage_b[DKV_STAGE_BYTES];
+    // Separate arrays (not one array with parts): the compiler must see that the direct-to-LDS copy of a coming
+    // tile cannot alias the reads of the tiles in use, or it waits for the copy too early.
+    __shared__ __attribute__((aligned(16))) char st0[DKV_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char st1[DKV_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char st2[DKV_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char exch[DKV_STAGE_BYTES];
     const int id = blockIdx.x;
     const bool head = id < head_blocks;
-    dkv_body<FUSED_HEADS>(b, delta, head ? id : id - head_blocks, head, wl, capacity, stage_a, stage_b);
+    dkv_body<FUSED_HEADS>(b, delta, head ? id : id - head_blocks, head, wl, capacity, st0, st1, st2, exch);
 }
 
 // =====================================================================================================
@@ -597,13 +663,13 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     if (fused) {
         // Fused mode updates dK/dV with plain read-modify-write: head blocks and main blocks of key tile 0 must
         // not run concurrently, so they get launches of their own (stream order).
-        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 256, 0, s>>>(b, ws.delta, 0, nullptr, 0);
+        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, 0, nullptr, 0);
         e = hipGetLastError();
         if (hook.stop) (void)hipEventRecord(hook.stop, s);
         if (e != hipSuccess) return e;
-        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 256, 0, s>>>(b, ws.delta, head_dkv, nullptr, 0);
+        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, head_dkv, nullptr, 0);
     } else {
-        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 256, 0, s>>>(b, ws.delta, head_dkv, ws.worklist,
+        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, head_dkv, ws.worklist,
                                                                                      (int)ws.worklist_items);
         if (hook.stop) (void)hipEventRecord(hook.stop, s);
     }

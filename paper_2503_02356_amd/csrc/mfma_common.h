@@ -99,20 +99,21 @@ __device__ __forceinline__ LaneOffsets lane_offsets()
 // Index of this wavefront inside its workgroup, as a value the compiler knows to be wave-uniform.
 __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
-// Direct global -> LDS copy of a swizzled tile of ROWS x 256 bytes by a 4-wavefront workgroup
+// Direct global -> LDS copy of a swizzled tile of ROWS x 256 bytes by a workgroup of WAVES wavefronts
 // (global_load_lds_dwordx4: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
 // one instruction fills 4 tile rows and the swizzle is applied on the global side: the lane that fills
 // physical unit u' of row r fetches logical unit u' ^ swz(r)).
-// A tile takes ROWS/16 instructions per wavefront (PARTS); each costs the issuing wavefront some 30-45 clocks
+// A tile takes ROWS / (4 * WAVES) instructions per wavefront (PARTS); each costs the issuing wavefront some 30-45 clocks
 // wherever it is placed (measured), so they are simply issued together at the start of a tile.
 // Per tile the source is a wave-uniform pointer to logical row 0 (scalar address arithmetic); rows beyond
 // last_row (relative to src) re-read last_row (the caller masks them).
 // Completion is tracked by vmcnt: wait_lds_dma() before the barrier that publishes the tile.
-template <int ROWS>
+template <int ROWS, int WAVES = 4>
 struct TileDma {
-    static constexpr int PARTS = ROWS / 16;
+    static constexpr int PARTS = ROWS / (4 * WAVES);
+    static_assert(PARTS >= 1 && (4 * WAVES) % 16 == 0, "a part must cover whole swizzle periods");
     unsigned row_bytes, unit16;   // unit16: byte offset of this lane's 16-byte unit inside its row (same for all parts)
-    int r0;                       // this lane's row in part 0; part c adds 16 rows
+    int r0;                       // this lane's row in part 0; part c adds 4 * WAVES rows
 
     __device__ __forceinline__ void init(int64_t row_bytes_)
     {
@@ -123,9 +124,9 @@ struct TileDma {
     }
     __device__ __forceinline__ void issue_part(const char *src, int last_row, char *lds_tile, int c) const
     {
-        const char *g = src + ((unsigned)min(r0 + 16 * c, last_row) * row_bytes + unit16);
+        const char *g = src + ((unsigned)min(r0 + 4 * WAVES * c, last_row) * row_bytes + unit16);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                         (CF_LDS void *)(lds_tile + (c * 4 + wave_id()) * 1024), 16, 0, 0);
+                                         (CF_LDS void *)(lds_tile + (c * WAVES + wave_id()) * 1024), 16, 0, 0);
     }
     __device__ __forceinline__ void issue(const char *src, int last_row, char *lds_tile) const
     {
