@@ -186,14 +186,15 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     const LaneOffsets lo = lane_offsets();
     char *exch = exch_all + pw * 2 * EXCH_SLOT_BYTES + lane * 16;   // this lane's 16 bytes of row group 0, slot 0
 
-    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles (all 8 wavefronts
-    // issue their share); LSE and delta go through one register of threads 0..63 / 64..127, loaded when the copy
-    // starts and turned into their LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0
+    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles (issued by the role-1
+    // wavefronts); LSE and delta go through one register of 64 + 64 threads, loaded when the copy starts and turned
+    // into their LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0
     // there) one step later, so that nothing waits for memory right after the copies start.
-    const float *stat_src = tid < 64 ? p.lse : delta;
-    TileDma<BQ, DKV_WAVES> dma_q, dma_do;
-    dma_q.init(p.q_stride_tok * 2);
-    dma_do.init(b.do_stride_tok * 2);
+    const int stid = tid - 256;                      // threads 256..319 / 320..383 (role 1) carry LSE / delta
+    const float *stat_src = stid < 64 ? p.lse : delta;
+    TileDma<BQ, 4> dma_q, dma_do;                    // the four role-1 wavefronts copy (their VALU load is the lighter one)
+    dma_q.init(p.q_stride_tok * 2, pw);
+    dma_do.init(b.do_stride_tok * 2, pw);
     int nx_h = h_first, nx_qt = qt_first;            // the tile the next copy fetches (advances by additions only)
     int stat_q0 = 0;                                 // first row of the tile the pending stat register belongs to
     float stat = 0.f;
@@ -203,7 +204,7 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
         dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
                      stage + QTILE_BYTES);
-        if (tid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
+        if (stid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
         stat_q0 = q0;
         if (++nx_qt == qt_end) {
             nx_qt = qt_first;
@@ -211,37 +212,54 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         }
     };
     auto publish_stats = [&](char *stage) {
-        if (tid < 128) {
+        if (stid < 128) {
             const bool live = stat_q0 + (tid & 63) < lq;
-            const float v = tid < 64 ? (live ? stat * kLog2e : INFINITY) : (live ? stat : 0.f);
-            ((float *)(stage + 2 * QTILE_BYTES))[tid] = v;
+            const float v = stid < 64 ? (live ? stat * kLog2e : INFINITY) : (live ? stat : 0.f);
+            ((float *)(stage + 2 * QTILE_BYTES))[stid] = v;
         }
     };
 
-    issue_tile(st0);
-    publish_stats(st0);
-    if (n_tiles > 1) {
-        issue_tile(st1);
-        publish_stats(st1);
+    if (role == 1) {
+        issue_tile(st0);
+        publish_stats(st0);
+        if (n_tiles > 1) {
+            issue_tile(st1);
+            publish_stats(st1);
+        }
+        wait_lds_dma();
     }
-    wait_lds_dma();
     __syncthreads();
 
     int cur_qt = qt_first;                           // query tile of the block this wavefront works on
 
     // role 0, block kb of the tile in `stage`: S, P (to the exchange slot), dV
-    auto block_p_dv = [&](int kb, const char *stage, char *slot) {
-        const int mb = kb & 1, q0 = cur_qt * BQ;
-        const char *qs = stage, *dos = stage + QTILE_BYTES;
-        const float *lse_s = (const float *)(stage + 2 * QTILE_BYTES);
-        bf16x8 aq[8];
+    // Operands that a wavefront requests at the END of a step for its next block, so that the LDS latency passes
+    // while it waits at the barrier: role 0 the Q rows of block k + 1, role 1 the transposed Q operands of block k.
+    bf16x8 aq[8], t_q[2][4];
+    auto fetch_q_rows = [&](int kb, const char *stage) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(qs + mb * 8192 + lo.row_unit[ks]);
+        for (int ks = 0; ks < 8; ++ks) aq[ks] = lds_read_b128(stage + (kb & 1) * 8192 + lo.row_unit[ks]);
+    };
+    // next_stage: stage of block kb + 1 (its tile is resident one step ahead), or nullptr after the last block
+    auto block_p_dv = [&](int kb, const char *stage, char *slot, const char *next_stage) {
+        const int mb = kb & 1, q0 = cur_qt * BQ;
+        const char *dos = stage + QTILE_BYTES;
+        const float *lse_s = (const float *)(stage + 2 * QTILE_BYTES);
         f32x16 s;
 #pragma unroll
         for (int j = 0; j < 16; ++j) s[j] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) s = mfma32(aq[ks], wf[ks], s);
+        // transposed operands of the second product, requested now so that they arrive during the arithmetic:
+        // k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
+        bf16x8 t_do[2][4];
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ta = mb * 8192 + tq * 4096;
+                t_do[tq][j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
+            }
         // P: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key.  The causal
         // mask is a select on every block (no branch around arithmetic that feeds the MFMAs).
         const int lim = kv_idx - off - q0 - mb * 32 - half * 4;   // masked iff lim > 8*g4 + j
@@ -261,26 +279,21 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         // dV_w^T += dO^T P : contraction over these 32 query rows in 2 groups of 16
 #pragma unroll
         for (int tq = 0; tq < 2; ++tq) {
-            // transposed operands: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
-            bf16x8 t_do[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int ta = mb * 8192 + tq * 4096;
-                t_do[j] = lds_read_tr_pair(dos + ta + lo.tr_lo[j], dos + ta + lo.tr_hi[j]);
-            }
             const bf16x8 pb = pack8(s[8 * tq + 0], s[8 * tq + 1], s[8 * tq + 2], s[8 * tq + 3], s[8 * tq + 4],
                                     s[8 * tq + 5], s[8 * tq + 6], s[8 * tq + 7]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[j], pb, acc[j]);
+            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[tq][j], pb, acc[j]);
             if (HEAD_TILES) {   // add the bf16 rounding residual of P
                 bf16x8 pl;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pl[e] = (__bf16)(s[8 * tq + e] - (float)pb[e]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[j], pl, acc[j]);
+                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_do[tq][j], pl, acc[j]);
             }
         }
         if (mb && ++cur_qt == qt_end) cur_qt = qt_first;
+        __builtin_amdgcn_sched_barrier(0);
+        if (kb + 1 < n_blk) fetch_q_rows(kb + 1, next_stage);
     };
     // role 1 works on two blocks per step, ordered so that its phases fall into the gaps of role 0's (which runs
     // S-MFMAs, P arithmetic, dV-MFMAs in that order): first the dS arithmetic of block k - 1 (while role 0 multiplies),
@@ -289,52 +302,64 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     f32x16 dp;
 #pragma unroll
     for (int j = 0; j < 16; ++j) dp[j] = 0.f;
-    auto finish_ds_dk = [&](int kb, const char *stage, const char *slot) {
+    // transposed Q operands of block kb: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
+    auto fetch_q_transposed = [&](int kb, const char *stage) {
+#pragma unroll
+        for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ta = (kb & 1) * 8192 + tq * 4096;
+                t_q[tq][j] = lds_read_tr_pair(stage + ta + lo.tr_lo[j], stage + ta + lo.tr_hi[j]);
+            }
+    };
+    // dO rows of block kb (A operand of dP), requested before the dK MFMAs of the previous block are issued
+    bf16x8 ado[8];
+    auto fetch_do_rows = [&](int kb, const char *stage) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) ado[ks] = lds_read_b128(stage + QTILE_BYTES + (kb & 1) * 8192 + lo.row_unit[ks]);
+    };
+    // next_stage: stage of block kb + 1 (for its dO rows), or nullptr
+    auto finish_ds_dk = [&](int kb, const char *stage, const char *slot, const char *next_stage) {
         const int mb = kb & 1;
-        const char *qs = stage;
         const float *del_s = (const float *)(stage + 2 * QTILE_BYTES) + 64;
+        // P and delta; the transposed operands of dK were requested at the end of the previous step.
+        f32x4 d4[4], p4[4];
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-            const f32x4 d4 = *(const f32x4 *)(del_s + mb * 32 + g4 * 8 + half * 4);
-            const f32x4 p4 = *(const f32x4 *)(slot + g4 * 1024);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) dp[g4 * 4 + j] = p4[j] * (dp[g4 * 4 + j] - d4[j]);
+            d4[g4] = *(const f32x4 *)(del_s + mb * 32 + g4 * 8 + half * 4);
+            p4[g4] = *(const f32x4 *)(slot + g4 * 1024);
         }
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dp[g4 * 4 + j] = p4[g4][j] * (dp[g4 * 4 + j] - d4[g4][j]);
         __builtin_amdgcn_sched_barrier(0);
+        if (kb + 1 < n_blk) fetch_do_rows(kb + 1, next_stage);
         // dK_w^T += Q^T dS : contraction over these 32 query rows in 2 groups of 16
 #pragma unroll
         for (int tq = 0; tq < 2; ++tq) {
-            // transposed operands: k-slot 8*half + e of group tq is query row 32*mb + 16*tq + (e/4)*8 + 4*half + e%4
-            bf16x8 t_q[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int ta = mb * 8192 + tq * 4096;
-                t_q[j] = lds_read_tr_pair(qs + ta + lo.tr_lo[j], qs + ta + lo.tr_hi[j]);
-            }
             const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3], dp[8 * tq + 4],
                                      dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[j], dsb, acc[j]);
+            for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[tq][j], dsb, acc[j]);
             if (HEAD_TILES) {   // add the bf16 rounding residual of dS
                 bf16x8 dl;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[j], dl, acc[j]);
+                for (int j = 0; j < 4; ++j) acc[j] = mfma32(t_q[tq][j], dl, acc[j]);
             }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
+    // dP of block kb from the dO rows already requested; then request the transposed Q operands of the same block
     auto start_dp = [&](int kb, const char *stage) {
-        const int mb = kb & 1;
-        const char *dos = stage + QTILE_BYTES;
-        bf16x8 ado[8];
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) ado[ks] = lds_read_b128(dos + mb * 8192 + lo.row_unit[ks]);
 #pragma unroll
         for (int j = 0; j < 16; ++j) dp[j] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) dp = mfma32(ado[ks], wf[ks], dp);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch_q_transposed(kb, stage);
     };
 
     // Step k of n_blk + 1.  s_cur: stage of tile k/2 (role 0's block), s_prev: stage of tile (k-1)/2 (role 1's older
@@ -343,16 +368,17 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     // occupy registers in the other.
     auto run = [&](auto role_tag) {
         constexpr int ROLE = decltype(role_tag)::value;
-        auto step = [&](int k, const char *s_cur, const char *s_prev, char *s_next) {
+        // s_cur1: stage of block k + 1
+        auto step = [&](int k, const char *s_cur, const char *s_prev, char *s_next, const char *s_cur1) {
             const bool odd = k & 1;
-            if (odd && (k + 3) / 2 < n_tiles) issue_tile(s_next);
+            if (ROLE == 1 && odd && (k + 3) / 2 < n_tiles) issue_tile(s_next);
             if (ROLE == 0) {
-                if (k < n_blk) block_p_dv(k, s_cur, exch + (k & 1) * EXCH_SLOT_BYTES);
+                if (k < n_blk) block_p_dv(k, s_cur, exch + (k & 1) * EXCH_SLOT_BYTES, s_cur1);
             } else {
-                if (k >= 1) finish_ds_dk(k - 1, s_prev, exch + ((k - 1) & 1) * EXCH_SLOT_BYTES);
+                if (k >= 1) finish_ds_dk(k - 1, s_prev, exch + ((k - 1) & 1) * EXCH_SLOT_BYTES, s_cur);
                 if (k < n_blk) start_dp(k, s_cur);
             }
-            if (!odd) {                              // the copy started one step ago has had a full step to land
+            if (ROLE == 1 && !odd) {                 // the copy started one step ago has had a full step to land
                 if (k >= 2 && (k + 2) / 2 < n_tiles) publish_stats(const_cast<char *>(s_cur == st0 ? st1 : s_cur == st1 ? st2 : st0));
                 wait_lds_dma();
             }
@@ -360,16 +386,21 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         };
         // Six steps = three tiles per trip, so that every stage is a compile-time array in every position.
         for (int k = 0; k <= n_blk; k += 6) {
-            step(k, st0, st2, nullptr);
-            if (k + 1 <= n_blk) step(k + 1, st0, st0, st2);
-            if (k + 2 <= n_blk) step(k + 2, st1, st0, nullptr);
-            if (k + 3 <= n_blk) step(k + 3, st1, st1, st0);
-            if (k + 4 <= n_blk) step(k + 4, st2, st1, nullptr);
-            if (k + 5 <= n_blk) step(k + 5, st2, st2, st1);
+            step(k, st0, st2, nullptr, st0);
+            if (k + 1 <= n_blk) step(k + 1, st0, st0, st2, st1);
+            if (k + 2 <= n_blk) step(k + 2, st1, st0, nullptr, st1);
+            if (k + 3 <= n_blk) step(k + 3, st1, st1, st0, st2);
+            if (k + 4 <= n_blk) step(k + 4, st2, st1, nullptr, st2);
+            if (k + 5 <= n_blk) step(k + 5, st2, st2, st1, st0);
         }
     };
-    if (role == 0) run(std::integral_constant<int, 0>());
-    else run(std::integral_constant<int, 1>());
+    if (role == 0) {
+        fetch_q_rows(0, st0);
+        run(std::integral_constant<int, 0>());
+    } else {
+        fetch_do_rows(0, st0);
+        run(std::integral_constant<int, 1>());
+    }
 
     // dK, dV: lane = key row; register group g4 of accumulator j = 4 consecutive d starting at 32*j + 8*g4 + 4*half.
     // Each wavefront turns its 32 x 128 block around in LDS (its own 16.5 KB half of a stage / of the exchange area,

@@ -114,19 +114,23 @@ struct TileDma {
     static_assert(PARTS >= 1 && (4 * WAVES) % 16 == 0, "a part must cover whole swizzle periods");
     unsigned row_bytes, unit16;   // unit16: byte offset of this lane's 16-byte unit inside its row (same for all parts)
     int r0;                       // this lane's row in part 0; part c adds 4 * WAVES rows
+    int wv;                       // index of this wavefront among the copying ones
 
-    __device__ __forceinline__ void init(int64_t row_bytes_)
+    // wave: index of the calling wavefront among the WAVES that copy (wave-uniform)
+    __device__ __forceinline__ void init(int64_t row_bytes_, int wave)
     {
         const int lane = threadIdx.x & 63;
         row_bytes = (unsigned)row_bytes_;
-        r0 = 4 * wave_id() + (lane >> 4);
+        wv = wave;
+        r0 = 4 * wave + (lane >> 4);
         unit16 = ((lane & 15) ^ swz(r0)) * 16;       // swz() has period 16 rows
     }
+    __device__ __forceinline__ void init(int64_t row_bytes_) { init(row_bytes_, wave_id()); }
     __device__ __forceinline__ void issue_part(const char *src, int last_row, char *lds_tile, int c) const
     {
         const char *g = src + ((unsigned)min(r0 + 4 * WAVES * c, last_row) * row_bytes + unit16);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                         (CF_LDS void *)(lds_tile + (c * WAVES + wave_id()) * 1024), 16, 0, 0);
+                                         (CF_LDS void *)(lds_tile + (c * WAVES + wv) * 1024), 16, 0, 0);
     }
     __device__ __forceinline__ void issue(const char *src, int last_row, char *lds_tile) const
     {
