@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--streams", type=int, default=3, help="HIP streams the dependency groups are dealt over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-pairs", type=float, default=3e7, help="unmasked pairs in the oracle's timed sample")
     args = ap.parse_args()
@@ -86,7 +87,7 @@ def main():
     plan = B.cf_build_chunks(lens, C)
     plan_ms = (time.perf_counter() - t0) * 1e3
     vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
-    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"]).load(vals)
+    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams).load(vals)
     pairs = eng.total_pairs
     flop_step = 14.0 * D * Hq * pairs
 
@@ -165,7 +166,7 @@ def main():
            "config": {"workload": args.workload, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "chunk_size": C,
                       "n_sequences": int(len(lens)), "n_chunks": n_chunks, "tokens": int(plan.total_tokens),
                       "unmasked_pairs": int(pairs), "flop_per_step": flop_step, "seed": args.seed,
-                      "plan_build_ms": plan_ms},
+                      "plan_build_ms": plan_ms, "streams": args.streams},
            "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
            "fwd_only": {"ms": fwd_pass_ms, "tflops": 4.0 * D * Hq * pairs / (fwd_pass_ms * 1e-3) / 1e12},
            "bwd_only": {"ms": bwd_pass_ms, "tflops": 10.0 * D * Hq * pairs / (bwd_pass_ms * 1e-3) / 1e12,

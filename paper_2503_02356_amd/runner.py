@@ -12,8 +12,13 @@ from . import binding as B
 
 
 class ChunkAttention:
-    def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0):
+    def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0,
+                 n_streams=1):
+        """n_streams > 1: dependency groups are dealt over that many HIP streams (default priority), so that
+        the last, partly filled wave of workgroups of one chunk's kernel overlaps with the next group's
+        kernels.  The chunks of one group stay on one stream, in the order of section 4.2."""
         self.plan, self.Hq, self.Hkv, self.D = plan, n_q_heads, n_kv_heads, head_dim
+        self.n_streams = max(1, int(n_streams))
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(head_dim))
         self.dev, self.flags = torch.device(device), flags
@@ -85,9 +90,19 @@ class ChunkAttention:
                                           self.scale, self.flags)
             ws_bytes = max(ws_bytes, B.cf_attn_bwd_workspace_bytes(ch["fwd"]))
             self.chunks.append(ch)
-        self.workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        # one backward workspace per stream: calls on different streams overlap
+        self.workspaces = [torch.empty(ws_bytes, dtype=torch.uint8, device=dev) for _ in range(self.n_streams)]
+        self.streams = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        # groups go, in plan order, to the stream with the least work so far (work = unmasked pairs)
+        load, lane_of = [0] * self.n_streams, {}
         for ch in self.chunks:
-            ch["bwd"] = B.make_bwd_params(ch["fwd"], ch["d_o"], ch["d_q"], ch["dk"], ch["dv"], self.workspace)
+            if ch["group"] not in lane_of:
+                lane_of[ch["group"]] = load.index(min(load))
+            load[lane_of[ch["group"]]] += ch["pairs"]
+        for ch in self.chunks:
+            ch["lane"] = lane_of[ch["group"]]
+            ch["bwd"] = B.make_bwd_params(ch["fwd"], ch["d_o"], ch["d_q"], ch["dk"], ch["dv"],
+                                          self.workspaces[ch["lane"]])
         self.total_pairs = sum(ch["pairs"] for ch in self.chunks)
         return self
 
@@ -105,22 +120,38 @@ class ChunkAttention:
     def backward_order(self):
         return [c for g in range(self.plan.n_groups) for c in reversed(self.plan.group(g))]
 
-    def run_forward(self, stream=None):
-        for c in self.forward_order():          # ascending inside each group
-            B.cf_attn_fwd(self.chunks[c]["fwd"], stream)
+    def _launch(self, ops):
+        """ops: iterable of (is_backward, chunk id) in issue order.  One stream: plain launches on the current
+        stream.  Several: every side stream first waits for what the current stream has queued, and the current
+        stream waits for all of them at the end, so callers see ordinary stream semantics."""
+        if not self.streams:
+            for bwd, c in ops:
+                (B.cf_attn_bwd if bwd else B.cf_attn_fwd)(self.chunks[c]["bwd" if bwd else "fwd"])
+            return
+        cur = torch.cuda.current_stream()
+        start = torch.cuda.Event()
+        start.record(cur)
+        for st in self.streams:
+            st.wait_event(start)
+        for bwd, c in ops:
+            ch = self.chunks[c]
+            handle = B.C.c_void_p(self.streams[ch["lane"]].cuda_stream)
+            (B.cf_attn_bwd if bwd else B.cf_attn_fwd)(ch["bwd" if bwd else "fwd"], handle)
+        for st in self.streams:
+            done = torch.cuda.Event()
+            done.record(st)
+            cur.wait_event(done)
 
-    def run_backward(self, stream=None):
-        for c in self.backward_order():         # descending inside each group
-            B.cf_attn_bwd(self.chunks[c]["bwd"], stream)
+    def run_forward(self):
+        self._launch((False, c) for c in self.forward_order())          # ascending inside each group
 
-    def run_schedule(self, K, stream=None):
+    def run_backward(self):
+        self._launch((True, c) for c in self.backward_order())          # descending inside each group
+
+    def run_schedule(self, K):
         """Algorithm 2 with K kept chunks: chunks marked FWD_DISCARD run forward (their K/V state is
         what later chunks need) and run forward again right before their backward."""
-        for op, c in self.plan.schedule(K):
-            if op == B.CF_OP_BWD:
-                B.cf_attn_bwd(self.chunks[c]["bwd"], stream)
-            else:
-                B.cf_attn_fwd(self.chunks[c]["fwd"], stream)
+        self._launch((op == B.CF_OP_BWD, c) for op, c in self.plan.schedule(K))
 
     # ------------------------------------------------------------------ results
     def results(self):
