@@ -180,7 +180,7 @@ int cf_attn_bwd(const cf_attn_bwd_params *p, void *hip_stream);
  * Measurement aid (not part of the paper's method): when both events (hipEvent_t, created by the
  * caller with timing enabled) are non-NULL, the NEXT cf_attn_fwd / cf_attn_bwd call on this thread
  * records `start` right before and `stop` right after its main kernel (forward: the attention
- * kernel; backward: the dK/dV/dQ kernel, without the delta and dQ-convert kernels) on that call's
+ * kernel; backward: the dK/dV kernel, without the dQ kernel that runs before it) on that call's
  * stream, then the hook clears itself.  Passing NULLs clears it.  Never fails.
  */
 int cf_profile_next_call(void *start_event, void *stop_event);
