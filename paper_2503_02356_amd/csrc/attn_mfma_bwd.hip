@@ -543,7 +543,7 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 #pragma unroll
                 for (int e = 0; e < 8; ++e) dlt = __builtin_fmaf((float)of[e], (float)dof[ks][e], dlt);
             }
-            dlt += __shfl_xor(dlt, 32);
+            dlt = sum_with_other_half(dlt);
             if (iq < lq && half == 0) delta[stat_at] = dlt;
         }
     }
@@ -626,7 +626,7 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     };
     if (HEAD_TILES) {
         sweep(std::true_type());
-        dlt = dsum + __shfl_xor(dsum, 32);           // the two lane halves hold different keys of the same row
+        dlt = sum_with_other_half(dsum);             // the two lane halves hold different keys of the same row
         if (wave_active && iq < lq && half == 0) delta[stat_at] = dlt;
     }
     sweep(std::false_type());

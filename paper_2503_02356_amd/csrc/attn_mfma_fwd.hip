@@ -120,7 +120,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
             for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s[0][i]);
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = max_with_other_half(mx);
             const float m_new = fmaxf(m_run, mx * c2);
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // first tile: exp2(-inf) = 0
             m_run = m_new;
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     }
 
     if (!wave_active) return;
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_with_other_half(l_run);
     if (iq < lq) {
         const float inv = 1.f / l_tot;
         const int row = q_seg0 + iq;

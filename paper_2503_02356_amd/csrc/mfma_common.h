@@ -149,6 +149,20 @@ __device__ __forceinline__ T *uniform(T *p)
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
+// Lane l and lane l ^ 32 combine a value without going through LDS: v_permlane32_swap with both operands = x
+// returns (x of the lower half, x of the upper half) in every lane (checked on the device with a probe).
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_with_other_half(float x)
+{
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_with_other_half(float x)
+{
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Finds the tile a workgroup owns.  Tiles of `tile` rows are counted per segment over cu[0..n_seg]
 // and numbered from the LAST tile of the LAST segment backwards (the later tiles of a segment see more
 // keys, so the heaviest tiles get the lowest ranks and start first).  Every lane of every wavefront
