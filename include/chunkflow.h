@@ -101,6 +101,26 @@ typedef struct {
 } cf_sched_op;
 int cf_build_schedule(cf_plan *plan, int32_t K, const cf_sched_op **ops, int64_t *n_ops);
 
+/*
+ * What a schedule costs and holds (section 4.2: the first N-K chunks of a group run forward twice; the
+ * memory kept for the backward passes is bounded by K * ChunkSize).  Replays the ops of
+ * cf_build_schedule(plan, K): a FWD_KEEP op adds its chunk to the kept set, the chunk's BWD op removes it,
+ * a FWD_DISCARD op keeps nothing.
+ *   n_forward, n_backward   ops of each kind (FWD_KEEP + FWD_DISCARD, BWD)
+ *   n_reforward             forward ops beyond one per chunk (= sum over groups of max(0, N - K))
+ *   peak_kept_chunks        largest size of the kept set           (<= K when every group has >= K chunks ...
+ *   peak_kept_tokens        largest token count of the kept set     ... and always <= K * chunk_size)
+ *   state_tokens            largest key/value state alive at once: tokens of the longest split sequence
+ *                           (the state of a group is released when the group is done), 0 if none is split
+ * Errors as cf_build_schedule; NULL out -> CF_EINVAL.  The plan's stored schedule is replaced by this K's.
+ */
+typedef struct {
+    int64_t n_forward, n_backward, n_reforward;
+    int64_t peak_kept_chunks, peak_kept_tokens;
+    int64_t state_tokens;
+} cf_sched_stats;
+int cf_schedule_stats(cf_plan *plan, int32_t K, cf_sched_stats *out);
+
 /* ============================================================================================
  * Device kernels.
  * ========================================================================================== */

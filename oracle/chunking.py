@@ -109,3 +109,32 @@ def build_schedule(groups, K):
     for g in groups:
         ops += schedule_group(list(g["chunks"]), K)
     return ops
+
+
+def schedule_stats(chunks, groups, K):
+    """Replay of Algorithm 2's schedule (section 4.2): how many passes it takes and how much it keeps.
+
+    A FWD_KEEP op keeps its chunk's activations until that chunk's BWD op; FWD_DISCARD keeps nothing.
+    Section 4.2 states the two facts this measures: the first N-K chunks of a group run forward
+    twice, and the kept activations never exceed K chunks (memory governed by K * ChunkSize).
+    The key/value state of a split sequence lives as long as its group is being processed.
+    """
+    tokens = {i: c["tokens"] for i, c in enumerate(chunks)}
+    st = dict(n_forward=0, n_backward=0, n_reforward=0, peak_kept_chunks=0, peak_kept_tokens=0, state_tokens=0)
+    kept = set()
+    for op, c in build_schedule(groups, K):
+        if op == BWD:
+            st["n_backward"] += 1
+            kept.remove(c)
+        else:
+            st["n_forward"] += 1
+            if op == FWD_KEEP:
+                kept.add(c)
+                st["peak_kept_chunks"] = max(st["peak_kept_chunks"], len(kept))
+                st["peak_kept_tokens"] = max(st["peak_kept_tokens"], sum(tokens[x] for x in kept))
+    assert not kept
+    st["n_reforward"] = st["n_forward"] - len(chunks)
+    for g in groups:
+        if g["seq_id"] >= 0:
+            st["state_tokens"] = max(st["state_tokens"], sum(tokens[c] for c in g["chunks"]))
+    return st

@@ -17,7 +17,7 @@ CF_FLAG_SCALAR_KERNELS = 1
 CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
 EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_plan_free", "cf_plan_get",
-           "cf_build_schedule", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_count_pairs", "cf_profile_next_call"]
+           "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_count_pairs", "cf_profile_next_call"]
 
 
 class CfError(RuntimeError):
@@ -39,6 +39,11 @@ class PlanView(C.Structure):
 
 class SchedOp(C.Structure):
     _fields_ = [("op", C.c_int32), ("reserved", C.c_int32), ("chunk", C.c_int64)]
+
+
+class SchedStats(C.Structure):
+    _fields_ = [("n_forward", C.c_int64), ("n_backward", C.c_int64), ("n_reforward", C.c_int64),
+                ("peak_kept_chunks", C.c_int64), ("peak_kept_tokens", C.c_int64), ("state_tokens", C.c_int64)]
 
 
 class AttnFwdParams(C.Structure):
@@ -140,6 +145,12 @@ class Plan:
         ops, n = C.POINTER(SchedOp)(), C.c_int64()
         _check(lib().cf_build_schedule(self._h, int(K), C.byref(ops), C.byref(n)))
         return [(ops[i].op, ops[i].chunk) for i in range(n.value)]
+
+    def schedule_stats(self, K):
+        """cf_schedule_stats as a dict."""
+        st = SchedStats()
+        _check(lib().cf_schedule_stats(self._h, int(K), C.byref(st)))
+        return {name: int(getattr(st, name)) for name, _ in SchedStats._fields_}
 
     def close(self):
         if self._h:

@@ -194,6 +194,42 @@ extern "C" int cf_build_schedule(cf_plan *p, int32_t K, const cf_sched_op **ops,
     return CF_OK;
 }
 
+extern "C" int cf_schedule_stats(cf_plan *p, int32_t K, cf_sched_stats *out)
+{
+    if (!out) return cf::fail(CF_EINVAL, "cf_schedule_stats: NULL out");
+    const cf_sched_op *ops = nullptr;
+    int64_t n_ops = 0;
+    if (int rc = cf_build_schedule(p, K, &ops, &n_ops)) return rc;
+    cf_sched_stats st = {};
+    int64_t kept_chunks = 0, kept_tokens = 0;
+    for (int64_t i = 0; i < n_ops; ++i) {
+        const int64_t tokens = p->chunk_tokens[ops[i].chunk];
+        if (ops[i].op == CF_OP_BWD) {
+            ++st.n_backward;
+            --kept_chunks;
+            kept_tokens -= tokens;
+        } else {
+            ++st.n_forward;
+            if (ops[i].op == CF_OP_FWD_KEEP) {
+                ++kept_chunks;
+                kept_tokens += tokens;
+                if (kept_chunks > st.peak_kept_chunks) st.peak_kept_chunks = kept_chunks;
+                if (kept_tokens > st.peak_kept_tokens) st.peak_kept_tokens = kept_tokens;
+            }
+        }
+    }
+    st.n_reforward = st.n_forward - (int64_t)p->chunk_tokens.size();
+    const int64_t n_groups = (int64_t)p->group_seq_id.size();
+    for (int64_t g = 0; g < n_groups; ++g) {
+        if (p->group_seq_id[g] < 0) continue;          // packed chunk: no state
+        int64_t len = 0;
+        for (int64_t j = p->group_chunk_ptr[g]; j < p->group_chunk_ptr[g + 1]; ++j) len += p->chunk_tokens[p->group_chunks[j]];
+        if (len > st.state_tokens) st.state_tokens = len;
+    }
+    *out = st;
+    return CF_OK;
+}
+
 extern "C" int64_t cf_count_pairs(const int32_t *cu_q, const int32_t *cu_k, int32_t n_segments)
 {
     if (!cu_q || !cu_k || n_segments < 0) return cf::fail(CF_EINVAL, "cf_count_pairs: bad argument");

@@ -11,6 +11,19 @@ import torch
 from . import binding as B
 
 
+def schedule_memory(plan, K, n_q_heads, n_kv_heads, head_dim, elem_bytes=2):
+    """Bytes the attention path holds under Algorithm 2 with K kept chunks (section 4.2: memory is
+    governed by K * ChunkSize, plus the key/value state of the sequence being processed).
+      kept_activation_bytes: Q, O (elem_bytes each) and LSE (fp32) of the kept chunks at the peak
+      state_bytes          : K, V (elem_bytes) and fp32 dK, dV of the longest split sequence
+    Only counts from cf_schedule_stats are used; nothing is allocated."""
+    st = plan.schedule_stats(K)
+    per_token = n_q_heads * (2 * head_dim * elem_bytes + 4)
+    per_state_token = n_kv_heads * head_dim * (2 * elem_bytes + 2 * 4)
+    return dict(st, kept_activation_bytes=st["peak_kept_tokens"] * per_token,
+                state_bytes=st["state_tokens"] * per_state_token)
+
+
 class ChunkAttention:
     def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0,
                  n_streams=1):

@@ -136,3 +136,46 @@ def test_schedule_whole_plan_groups_contiguous():
     assert seen_groups == sorted(seen_groups)
     with pytest.raises(ValueError):
         CK.build_schedule(groups, 0)
+
+
+# ---- schedule_stats: what section 4.2 says a schedule costs and keeps --------------------------------
+
+@pytest.mark.parametrize("N,K", [(1, 1), (4, 1), (4, 2), (4, 4), (4, 9), (8, 3)])
+def test_schedule_stats_single_long_sequence(N, K):
+    """One sequence of N full chunks (closed forms from section 4.2: the first N-K chunks run forward
+    twice; at most K chunks' activations are kept; the key/value state covers the whole sequence)."""
+    C = 16
+    chunks, groups = CK.build_chunks([N * C], C) if N > 1 else CK.build_chunks([C], C)
+    st = CK.schedule_stats(chunks, groups, K)
+    assert st["n_backward"] == N
+    assert st["n_reforward"] == max(0, N - K) and st["n_forward"] == N + max(0, N - K)
+    assert st["peak_kept_chunks"] == min(N, K) and st["peak_kept_tokens"] == min(N, K) * C
+    assert st["state_tokens"] == (N * C if N > 1 else 0)
+
+
+def test_schedule_stats_k1_keeps_one_chunk_at_a_time():
+    """Section 4.2 for K = 1: at any time at most one chunk's activations are stored, whatever the batch."""
+    rng = np.random.default_rng(5)
+    for _ in range(30):
+        lens = [int(x) for x in rng.integers(1, 200, size=rng.integers(1, 12))]
+        C = int(rng.integers(8, 64))
+        chunks, groups = CK.build_chunks(lens, C)
+        st = CK.schedule_stats(chunks, groups, 1)
+        assert st["peak_kept_chunks"] == 1 and st["peak_kept_tokens"] <= C
+        long_chunks = sum(len(g["chunks"]) - 1 for g in groups if g["seq_id"] >= 0)
+        assert st["n_reforward"] == long_chunks          # every chunk but the last of each split sequence
+
+
+def test_schedule_stats_kept_memory_follows_chunk_size():
+    """The trend of the paper's peak-memory table: with K fixed, a larger ChunkSize keeps more tokens
+    (the bound K * ChunkSize is reached as soon as a sequence is split), and K * ChunkSize bounds it."""
+    lens = [40000, 700, 3000, 12000, 250, 90, 5000]
+    peaks = []
+    for C in (2048, 4096, 8192):
+        chunks, groups = CK.build_chunks(lens, C)
+        for K in (1, 2, 4):
+            st = CK.schedule_stats(chunks, groups, K)
+            assert st["peak_kept_tokens"] <= K * C
+            assert st["state_tokens"] == 40000
+        peaks.append(CK.schedule_stats(chunks, groups, 1)["peak_kept_tokens"])
+    assert peaks == [2048, 4096, 8192]

@@ -116,3 +116,40 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     b = B.AttnBwdParams()
     assert B.lib().cf_attn_bwd(None, None) == B.CF_EINVAL
     assert B.lib().cf_attn_bwd(ctypes.byref(b), None) < 0
+
+
+@pytest.mark.parametrize("K", [1, 2, 3, 16])
+def test_schedule_stats_match_oracle(K):
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        lens = [int(x) for x in rng.integers(1, 400, size=rng.integers(1, 15))]
+        C = int(rng.integers(8, 96))
+        plan = B.cf_build_chunks(lens, C)
+        chunks, groups = CK.build_chunks(lens, C)
+        assert plan.schedule_stats(K) == CK.schedule_stats(chunks, groups, K)
+        plan.close()
+
+
+def test_schedule_stats_errors():
+    plan = B.cf_build_chunks([5, 9], 4)
+    with pytest.raises(B.CfError):
+        plan.schedule_stats(0)
+    assert B.lib().cf_schedule_stats(plan._h, 1, None) == -1
+    plan.close()
+
+
+def test_schedule_memory_is_bounded_by_k_times_chunk_size():
+    """Section 4.2: kept activations never exceed K chunks; the paper's peak-memory table grows with ChunkSize."""
+    from paper_2503_02356_amd.runner import schedule_memory
+    lens = [40000, 700, 3000, 12000, 250, 90, 5000]
+    prev = 0
+    for C in (2048, 4096, 8192):
+        plan = B.cf_build_chunks(lens, C)
+        m = schedule_memory(plan, 1, 28, 4, 128)
+        assert m["kept_activation_bytes"] == C * 28 * (2 * 128 * 2 + 4)
+        assert m["state_bytes"] == 40000 * 4 * 128 * (4 + 8)
+        assert m["kept_activation_bytes"] > prev
+        prev = m["kept_activation_bytes"]
+        m4 = schedule_memory(plan, 4, 28, 4, 128)
+        assert m4["kept_activation_bytes"] <= 4 * m["kept_activation_bytes"] and m4["n_reforward"] < m["n_reforward"]
+        plan.close()
