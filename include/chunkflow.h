@@ -197,6 +197,22 @@ int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p);
 int cf_attn_bwd(const cf_attn_bwd_params *p, void *hip_stream);
 
 /*
+ * Whole-plan launches: several chunks in one call.  The results are those of calling cf_attn_fwd /
+ * cf_attn_bwd for params[0], params[1], ... in that order on the stream (dK/dV that several chunks share --
+ * the chunks of one long sequence, section 4.2 -- accumulate in exactly that order).  What changes is the
+ * launch shape: for a run of consecutive chunks that take the bf16 head_dim-128 path with equal head counts
+ * (up to 16 forward, 8 backward), the forward kernels -- and in the backward the dQ kernels, which touch
+ * nothing another chunk's backward writes -- become ONE launch whose workgroups are dealt heaviest chunk
+ * first, so that the last, partly filled wave of workgroups of a big chunk is filled by the next chunk's
+ * instead of leaving compute units idle.  The dK/dV kernels still run chunk by chunk.
+ *   params  host array [n]; for the backward every chunk needs a workspace of its OWN (they are in use at
+ *           the same time; overlapping workspaces -> CF_EINVAL)
+ * Errors: as the single-chunk calls, checked for every chunk before anything is enqueued; n == 0 is a no-op.
+ */
+int cf_attn_fwd_batch(const cf_attn_fwd_params *params, int32_t n, void *hip_stream);
+int cf_attn_bwd_batch(const cf_attn_bwd_params *params, int32_t n, void *hip_stream);
+
+/*
  * Measurement aid (not part of the paper's method): when both events (hipEvent_t, created by the
  * caller with timing enabled) are non-NULL, the NEXT cf_attn_fwd / cf_attn_bwd call on this thread
  * records `start` right before and `stop` right after its main kernel (forward: the attention

@@ -17,7 +17,8 @@ CF_FLAG_SCALAR_KERNELS = 1
 CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
 EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_plan_free", "cf_plan_get",
-           "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_count_pairs", "cf_profile_next_call"]
+           "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_attn_fwd_batch", "cf_attn_bwd_batch",
+           "cf_count_pairs", "cf_profile_next_call"]
 
 
 class CfError(RuntimeError):
@@ -87,6 +88,9 @@ def lib():
         L.cf_attn_bwd_workspace_bytes.argtypes = [C.POINTER(AttnFwdParams)]
         L.cf_attn_bwd_workspace_bytes.restype = C.c_int64
         L.cf_attn_bwd.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
+        L.cf_attn_fwd_batch.argtypes = [C.POINTER(AttnFwdParams), C.c_int32, C.c_void_p]
+        L.cf_attn_bwd_batch.argtypes = [C.POINTER(AttnBwdParams), C.c_int32, C.c_void_p]
+        L.cf_schedule_stats.argtypes = [C.c_void_p, C.c_int32, C.POINTER(SchedStats)]
         L.cf_profile_next_call.argtypes = [C.c_void_p, C.c_void_p]
         L.cf_count_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.cf_count_pairs.restype = C.c_int64
@@ -241,6 +245,25 @@ def make_bwd_params(fwd_params, d_o, d_q, d_k, d_v, workspace):
     b.workspace, b.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     b._keepalive = (fwd_params, d_o, d_q, d_k, d_v, workspace)      # see make_fwd_params
     return b
+
+
+def params_array(params_list):
+    """A contiguous ctypes array holding copies of the given parameter structs (kept alive with their tensors)."""
+    if not params_list:
+        return None
+    arr = (type(params_list[0]) * len(params_list))(*params_list)
+    arr._keepalive = tuple(params_list)
+    return arr
+
+
+def cf_attn_fwd_batch(params_arr, stream=None):
+    n = len(params_arr) if params_arr is not None else 0
+    _check(lib().cf_attn_fwd_batch(params_arr, n, stream if stream is not None else _stream()))
+
+
+def cf_attn_bwd_batch(params_arr, stream=None):
+    n = len(params_arr) if params_arr is not None else 0
+    _check(lib().cf_attn_bwd_batch(params_arr, n, stream if stream is not None else _stream()))
 
 
 def cf_attn_bwd(params, stream=None):

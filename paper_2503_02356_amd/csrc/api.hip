@@ -1,6 +1,9 @@
 // C ABI of the device entry points: argument checks, workspace carving, kernel selection.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -101,9 +104,11 @@ extern "C" int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p)
     return delta_bytes(*p) + worklist_bytes(*p);
 }
 
-extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
+namespace {
+
+// Argument checks of one backward call; on success fills the scratch layout inside the caller's workspace.
+int check_bwd(const cf_attn_bwd_params *b, const char *who, cf::BwdWorkspace *ws)
 {
-    const char *who = "cf_attn_bwd";
     if (!b) return cf::fail(CF_EINVAL, "%s: params is NULL", who);
     if (int rc = check_fwd(&b->f, who, false)) return rc;
     const cf_attn_fwd_params &p = b->f;
@@ -124,13 +129,16 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
     if (b->workspace_bytes < need)
         return cf::fail(CF_EINVAL, "%s: workspace has %lld bytes, %lld needed", who, (long long)b->workspace_bytes,
                         (long long)need);
-    cf::BwdWorkspace ws;
-    ws.delta = static_cast<float *>(b->workspace);
-    ws.worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
-    ws.worklist_items = mfma_shape(p) ? cf::dkv_worklist_capacity(p) : 0;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    ws->delta = static_cast<float *>(b->workspace);
+    ws->worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
+    ws->worklist_items = mfma_shape(p) ? cf::dkv_worklist_capacity(p) : 0;
+    return CF_OK;
+}
+
+int bwd_one(const cf_attn_bwd_params *b, const cf::BwdWorkspace &ws, hipStream_t s, const char *who)
+{
     hipError_t e = hipSuccess;
-    if (use_mfma(p)) {
+    if (use_mfma(b->f)) {
         e = cf::launch_mfma_bwd(*b, ws, s);          // its dQ kernel forms delta itself
     } else {
         e = cf::launch_delta(*b, ws, s);
@@ -138,4 +146,96 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
         e = cf::launch_simple_bwd(*b, ws, s);
     }
     return e == hipSuccess ? CF_OK : hip_fail(who, e);
+}
+
+// Heaviest first: the order in which the workgroups of a fused launch are dealt (work ~ queries x keys).
+template <typename GetFwd>
+void heaviest_first(int *order, int n, GetFwd fwd)
+{
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order, order + n, [&](int a, int b) {
+        return (int64_t)fwd(a).n_tokens * fwd(a).n_kv_tokens > (int64_t)fwd(b).n_tokens * fwd(b).n_kv_tokens;
+    });
+}
+
+}  // namespace
+
+extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
+{
+    cf::BwdWorkspace ws;
+    if (int rc = check_bwd(b, "cf_attn_bwd", &ws)) return rc;
+    return bwd_one(b, ws, static_cast<hipStream_t>(hip_stream), "cf_attn_bwd");
+}
+
+extern "C" int cf_attn_fwd_batch(const cf_attn_fwd_params *params, int32_t n, void *hip_stream)
+{
+    const char *who = "cf_attn_fwd_batch";
+    if (n < 0 || (n > 0 && !params)) return cf::fail(CF_EINVAL, "%s: bad argument", who);
+    for (int32_t i = 0; i < n; ++i)
+        if (int rc = check_fwd(&params[i], who, false)) return rc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int32_t i = 0;
+    while (i < n) {
+        // a run of chunks the MFMA kernel covers with the same head counts becomes one launch
+        int32_t j = i;
+        while (j < n && j - i < cf::CF_FWD_BATCH_MAX && use_mfma(params[j]) && params[j].n_q_heads == params[i].n_q_heads &&
+               params[j].n_kv_heads == params[i].n_kv_heads)
+            ++j;
+        hipError_t e;
+        if (j - i >= 2) {
+            int order[cf::CF_FWD_BATCH_MAX];
+            heaviest_first(order, j - i, [&](int a) -> const cf_attn_fwd_params & { return params[i + a]; });
+            const cf_attn_fwd_params *chunks[cf::CF_FWD_BATCH_MAX];
+            for (int a = 0; a < j - i; ++a) chunks[a] = &params[i + order[a]];
+            e = cf::launch_mfma_fwd_batch(chunks, j - i, s);
+        } else {
+            j = i + 1;
+            e = use_mfma(params[i]) ? cf::launch_mfma_fwd(params[i], s) : cf::launch_simple_fwd(params[i], s);
+        }
+        if (e != hipSuccess) return hip_fail(who, e);
+        i = j;
+    }
+    return CF_OK;
+}
+
+extern "C" int cf_attn_bwd_batch(const cf_attn_bwd_params *params, int32_t n, void *hip_stream)
+{
+    const char *who = "cf_attn_bwd_batch";
+    if (n < 0 || (n > 0 && !params)) return cf::fail(CF_EINVAL, "%s: bad argument", who);
+    std::vector<cf::BwdWorkspace> ws;
+    try {
+        ws.resize((size_t)n);
+    } catch (const std::bad_alloc &) {
+        return cf::fail(CF_ENOMEM, "%s: out of host memory", who);
+    }
+    for (int32_t i = 0; i < n; ++i)
+        if (int rc = check_bwd(&params[i], who, &ws[i])) return rc;
+    // the chunks of one call run interleaved: their workspaces must not overlap
+    for (int32_t i = 0; i < n; ++i)
+        for (int32_t j = i + 1; j < n; ++j) {
+            const char *a = static_cast<const char *>(params[i].workspace), *b = static_cast<const char *>(params[j].workspace);
+            if (a < b + params[j].workspace_bytes && b < a + params[i].workspace_bytes)
+                return cf::fail(CF_EINVAL, "%s: chunks %d and %d share workspace memory", who, i, j);
+        }
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int32_t i = 0;
+    while (i < n) {
+        int32_t j = i;
+        while (j < n && j - i < cf::CF_BWD_BATCH_MAX && use_mfma(params[j].f) && params[j].f.n_q_heads == params[i].f.n_q_heads &&
+               params[j].f.n_kv_heads == params[i].f.n_kv_heads)
+            ++j;
+        if (j - i >= 2) {
+            int order[cf::CF_BWD_BATCH_MAX];
+            heaviest_first(order, j - i, [&](int a) -> const cf_attn_fwd_params & { return params[i + a].f; });
+            const cf_attn_bwd_params *chunks[cf::CF_BWD_BATCH_MAX];
+            for (int a = 0; a < j - i; ++a) chunks[a] = &params[i + a];
+            const hipError_t e = cf::launch_mfma_bwd_batch(chunks, &ws[i], order, j - i, s);
+            if (e != hipSuccess) return hip_fail(who, e);
+        } else {
+            j = i + 1;
+            if (int rc = bwd_one(&params[i], ws[i], s, who)) return rc;
+        }
+        i = j;
+    }
+    return CF_OK;
 }

@@ -658,6 +658,76 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, f
     dq_body(b, delta, head ? id : id - head_blocks, head, stage_a, stage_b);
 }
 
+// Several chunks in one launch (workgroups [first_block[c], first_block[c+1]) belong to chunk c, heaviest chunk
+// first): dQ and delta of a chunk depend on nothing another chunk's backward writes, so the last, partly filled
+// wave of workgroups of a big chunk can be filled by the next chunk's.
+struct DqBatch {
+    int n;
+    int first_block[CF_BWD_BATCH_MAX + 1];
+    int head_blocks[CF_BWD_BATCH_MAX];
+    float *delta[CF_BWD_BATCH_MAX];
+    cf_attn_bwd_params b[CF_BWD_BATCH_MAX];
+};
+__global__ __launch_bounds__(256, 2) void mfma_dq_batch_kernel(DqBatch q)
+{
+    __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
+    int c = 0;
+    while (c + 1 < q.n && (int)blockIdx.x >= q.first_block[c + 1]) ++c;
+    const int id = blockIdx.x - q.first_block[c];
+    const bool head = id < q.head_blocks[c];
+    dq_body(q.b[c], q.delta[c], head ? id : id - q.head_blocks[c], head, stage_a, stage_b);
+}
+
+// Launch geometry of one chunk's backward.
+struct BwdShape {
+    bool fused;              // dK/dV: one workgroup per key tile and kv head loops over the query heads (plain RMW)
+    int64_t dq_blocks, dkv_blocks;
+    int head_dq, head_dkv;
+    bool ok;
+};
+BwdShape bwd_shape(const cf_attn_fwd_params &p, const BwdWorkspace &ws)
+{
+    BwdShape g;
+    // Upper bounds on tile counts: sum_g ceil(L_g / tile) <= total / tile + n_segments.
+    const int64_t kv_tiles = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
+    const int64_t q_tiles = (int64_t)p.n_tokens / BM + p.n_segments;
+    // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
+    g.fused = kv_tiles * p.n_kv_heads >= 4096;
+    g.dq_blocks = q_tiles * p.n_q_heads;
+    g.head_dq = p.n_segments * p.n_q_heads;
+    g.head_dkv = p.n_segments * p.n_kv_heads;
+    g.dkv_blocks = (g.fused ? kv_tiles : ws.worklist_items) * p.n_kv_heads;
+    g.ok = g.dkv_blocks + g.head_dkv <= 0x7fffffffLL && g.dq_blocks + g.head_dq <= 0x7fffffffLL && ws.worklist_items <= 0x7fffffffLL;
+    return g;
+}
+
+hipError_t launch_worklist(const cf_attn_fwd_params &p, const BwdWorkspace &ws, const BwdShape &g, hipStream_t s)
+{
+    if (g.fused) return hipSuccess;
+    dkv_worklist_kernel<<<1, 1024, 0, s>>>(p, ws.worklist, (int)ws.worklist_items);
+    return hipGetLastError();
+}
+
+hipError_t launch_dkv(const cf_attn_bwd_params &b, const BwdWorkspace &ws, const BwdShape &g, const ProfileHook &hook, hipStream_t s)
+{
+    if (hook.start) (void)hipEventRecord(hook.start, s);
+    if (g.fused) {
+        // Fused mode updates dK/dV with plain read-modify-write: head blocks and main blocks of key tile 0 must
+        // not run concurrently, so they get launches of their own (stream order).
+        mfma_dkv_kernel<true><<<dim3((unsigned)g.dkv_blocks), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, 0, nullptr, 0);
+        const hipError_t e = hipGetLastError();
+        if (hook.stop) (void)hipEventRecord(hook.stop, s);
+        if (e != hipSuccess) return e;
+        mfma_dkv_kernel<true><<<dim3((unsigned)g.head_dkv), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, g.head_dkv, nullptr, 0);
+    } else {
+        mfma_dkv_kernel<false><<<dim3((unsigned)(g.dkv_blocks + g.head_dkv)), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, g.head_dkv, ws.worklist,
+                                                                                         (int)ws.worklist_items);
+        if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 int64_t dkv_worklist_capacity(const cf_attn_fwd_params &p)
@@ -669,42 +739,49 @@ int64_t dkv_worklist_capacity(const cf_attn_fwd_params &p)
 hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, hipStream_t s)
 {
     const cf_attn_fwd_params &p = b.f;
-    // Upper bounds on tile counts: sum_g ceil(L_g / tile) <= total / tile + n_segments.
-    const int64_t kv_tiles = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
-    const int64_t q_tiles = (int64_t)p.n_tokens / BM + p.n_segments;
-    // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
-    const bool fused = kv_tiles * p.n_kv_heads >= 4096;
-    const int64_t dq_blocks = q_tiles * p.n_q_heads;
-    const int head_dq = p.n_segments * p.n_q_heads;
-    const int head_dkv = p.n_segments * p.n_kv_heads;
-    const int64_t dkv_blocks = (fused ? kv_tiles : ws.worklist_items) * p.n_kv_heads;
-    if (dkv_blocks + head_dkv > 0x7fffffffLL || dq_blocks + head_dq > 0x7fffffffLL || ws.worklist_items > 0x7fffffffLL)
-        return hipErrorInvalidConfiguration;
+    const BwdShape g = bwd_shape(p, ws);
+    if (!g.ok) return hipErrorInvalidConfiguration;
     hipError_t e;
-    if (!fused) {
-        dkv_worklist_kernel<<<1, 1024, 0, s>>>(p, ws.worklist, (int)ws.worklist_items);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
+    if ((e = launch_worklist(p, ws, g, s)) != hipSuccess) return e;
     // dQ first: it also produces delta (main blocks: <dO, O>; head blocks: the exact sum for the head rows), which
     // the dK/dV kernel reads.
-    mfma_dq_kernel<<<dim3((unsigned)(dq_blocks + head_dq)), 256, 0, s>>>(b, ws.delta, head_dq);
+    mfma_dq_kernel<<<dim3((unsigned)(g.dq_blocks + g.head_dq)), 256, 0, s>>>(b, ws.delta, g.head_dq);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const ProfileHook hook = take_profile_hook();
-    if (hook.start) (void)hipEventRecord(hook.start, s);
-    if (fused) {
-        // Fused mode updates dK/dV with plain read-modify-write: head blocks and main blocks of key tile 0 must
-        // not run concurrently, so they get launches of their own (stream order).
-        mfma_dkv_kernel<true><<<dim3((unsigned)dkv_blocks), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, 0, nullptr, 0);
-        e = hipGetLastError();
-        if (hook.stop) (void)hipEventRecord(hook.stop, s);
-        if (e != hipSuccess) return e;
-        mfma_dkv_kernel<true><<<dim3((unsigned)head_dkv), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, head_dkv, nullptr, 0);
-    } else {
-        mfma_dkv_kernel<false><<<dim3((unsigned)(dkv_blocks + head_dkv)), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, head_dkv, ws.worklist,
-                                                                                     (int)ws.worklist_items);
-        if (hook.stop) (void)hipEventRecord(hook.stop, s);
+    return launch_dkv(b, ws, g, take_profile_hook(), s);
+}
+
+// Backward of 1..CF_BWD_BATCH_MAX chunks: work lists, ONE dQ launch over all chunks (dealt in the order of `dq_order`,
+// indices into chunks), then the dK/dV kernels chunk by chunk in the order of `chunks`, which is therefore the order
+// in which a shared dK/dV state accumulates.
+hipError_t launch_mfma_bwd_batch(const cf_attn_bwd_params *const *chunks, const BwdWorkspace *ws, const int *dq_order, int n,
+                                 hipStream_t s)
+{
+    if (n < 1 || n > CF_BWD_BATCH_MAX) return hipErrorInvalidValue;
+    BwdShape g[CF_BWD_BATCH_MAX];
+    hipError_t e;
+    for (int c = 0; c < n; ++c) {
+        g[c] = bwd_shape(chunks[c]->f, ws[c]);
+        if (!g[c].ok) return hipErrorInvalidConfiguration;
+        if ((e = launch_worklist(chunks[c]->f, ws[c], g[c], s)) != hipSuccess) return e;
     }
-    return hipGetLastError();
+    DqBatch q;
+    q.n = n;
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const int c = dq_order[i];
+        q.first_block[i] = (int)total;
+        q.head_blocks[i] = g[c].head_dq;
+        q.delta[i] = ws[c].delta;
+        q.b[i] = *chunks[c];
+        total += g[c].dq_blocks + g[c].head_dq;
+        if (total > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    }
+    q.first_block[n] = (int)total;
+    mfma_dq_batch_kernel<<<dim3((unsigned)total), 256, 0, s>>>(q);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    for (int c = 0; c < n; ++c)
+        if ((e = launch_dkv(*chunks[c], ws[c], g[c], ProfileHook(), s)) != hipSuccess) return e;
+    return hipSuccess;
 }
 
 }  // namespace cf

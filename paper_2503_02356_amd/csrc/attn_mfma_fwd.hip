@@ -23,19 +23,15 @@ constexpr int D = 128;
 constexpr int TILE_BYTES = BN * 256;          // one swizzled K or V tile (see mfma_common.h)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // K then V
 
-__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
+// id: index of the workgroup among those of this chunk
+__device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, char *stage_a, char *stage_b)
 {
-    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
-    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
-    __shared__ __attribute__((aligned(16))) char stage_a[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char stage_b[STAGE_BYTES];
     const int lane = threadIdx.x & 63, wave = wave_id();
     const int half = lane >> 5, col = lane & 31;
 
     // Block id -> (tile rank, head).  The key/value head varies fastest so that the workgroups an XCD
     // receives (ids are dealt round-robin over the 8 XCDs) keep re-reading the same K/V head in its L2.
     const int G = p.n_q_heads / p.n_kv_heads;
-    int id = blockIdx.x;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
     const int h = kh * G + id % G;
@@ -182,13 +178,58 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
     }
 }
 
+__global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)
+{
+    // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
+    // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
+    __shared__ __attribute__((aligned(16))) char stage_a[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[STAGE_BYTES];
+    fwd_body(p, blockIdx.x, stage_a, stage_b);
+}
+
+// Several chunks in one launch: workgroups [first_block[c], first_block[c+1]) belong to chunk c.  The host
+// puts the heaviest chunk first, so the last, partly filled wave of workgroups of a big chunk is filled by
+// the next chunk's workgroups instead of leaving compute units idle.
+struct FwdBatch {
+    int n;
+    int first_block[CF_FWD_BATCH_MAX + 1];
+    cf_attn_fwd_params p[CF_FWD_BATCH_MAX];
+};
+__global__ __launch_bounds__(256, 2) void mfma_fwd_batch_kernel(FwdBatch b)
+{
+    __shared__ __attribute__((aligned(16))) char stage_a[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char stage_b[STAGE_BYTES];
+    const int id = blockIdx.x;
+    int c = 0;
+    while (c + 1 < b.n && id >= b.first_block[c + 1]) ++c;
+    fwd_body(b.p[c], id - b.first_block[c], stage_a, stage_b);
+}
+
+// Upper bound on the number of 128-row tiles: sum_g ceil(Lq_g / BM) <= T / BM + n_segments.
+int64_t fwd_blocks(const cf_attn_fwd_params &p) { return ((int64_t)p.n_tokens / BM + p.n_segments) * p.n_q_heads; }
+
 }  // namespace
+
+hipError_t launch_mfma_fwd_batch(const cf_attn_fwd_params *const *chunks, int n, hipStream_t s)
+{
+    if (n < 1 || n > CF_FWD_BATCH_MAX) return hipErrorInvalidValue;
+    FwdBatch b;
+    b.n = n;
+    int64_t total = 0;
+    for (int c = 0; c < n; ++c) {
+        b.first_block[c] = (int)total;
+        b.p[c] = *chunks[c];
+        total += fwd_blocks(*chunks[c]);
+        if (total > 0x7fffffffLL) return hipErrorInvalidConfiguration;
+    }
+    b.first_block[n] = (int)total;
+    mfma_fwd_batch_kernel<<<dim3((unsigned)total), 256, 0, s>>>(b);
+    return hipGetLastError();
+}
 
 hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s)
 {
-    // Upper bound on the number of 128-row tiles: sum_g ceil(Lq_g / BM) <= T / BM + n_segments.
-    const int64_t tiles_max = (int64_t)p.n_tokens / BM + p.n_segments;
-    const int64_t blocks = tiles_max * p.n_q_heads;
+    const int64_t blocks = fwd_blocks(p);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidConfiguration;
     const ProfileHook hook = take_profile_hook();
     if (hook.start) (void)hipEventRecord(hook.start, s);

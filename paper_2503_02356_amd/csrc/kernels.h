@@ -34,6 +34,14 @@ hipError_t launch_delta(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hip
 
 // bf16 MFMA kernels, head_dim 128.
 hipError_t launch_mfma_fwd(const cf_attn_fwd_params &p, hipStream_t s);
+// Forward of 1..CF_FWD_BATCH_MAX chunks as one launch, workgroups dealt in the order of `chunks`.
+constexpr int CF_FWD_BATCH_MAX = 16;
+hipError_t launch_mfma_fwd_batch(const cf_attn_fwd_params *const *chunks, int n, hipStream_t s);
 hipError_t launch_mfma_bwd(const cf_attn_bwd_params &p, const BwdWorkspace &ws, hipStream_t s);
+// Backward of 1..CF_BWD_BATCH_MAX chunks: one dQ launch (workgroups dealt in the order dq_order, indices into
+// chunks), then the dK/dV kernels in the order of `chunks`.
+constexpr int CF_BWD_BATCH_MAX = 8;
+hipError_t launch_mfma_bwd_batch(const cf_attn_bwd_params *const *chunks, const BwdWorkspace *ws, const int *dq_order,
+                                 int n, hipStream_t s);
 
 }  // namespace cf

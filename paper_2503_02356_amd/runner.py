@@ -26,12 +26,15 @@ def schedule_memory(plan, K, n_q_heads, n_kv_heads, head_dim, elem_bytes=2):
 
 class ChunkAttention:
     def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0,
-                 n_streams=1):
+                 n_streams=1, fused_launch=False):
         """n_streams > 1: dependency groups are dealt over that many HIP streams (default priority), so that
         the last, partly filled wave of workgroups of one chunk's kernel overlaps with the next group's
         kernels.  The chunks of one group stay on one stream, in the order of section 4.2."""
         self.plan, self.Hq, self.Hkv, self.D = plan, n_q_heads, n_kv_heads, head_dim
         self.n_streams = max(1, int(n_streams))
+        # fused_launch: run_forward / run_backward hand the whole plan to cf_attn_fwd_batch / cf_attn_bwd_batch
+        # (one workspace per chunk); otherwise one cf_attn_fwd / cf_attn_bwd call per chunk.
+        self.fused_launch = bool(fused_launch)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(head_dim))
         self.dev, self.flags = torch.device(device), flags
@@ -114,8 +117,14 @@ class ChunkAttention:
             load[lane_of[ch["group"]]] += ch["pairs"]
         for ch in self.chunks:
             ch["lane"] = lane_of[ch["group"]]
+            if self.fused_launch:       # the chunks of a fused call are in flight together: a workspace each
+                need = B.cf_attn_bwd_workspace_bytes(ch["fwd"])
+                ch["workspace"] = torch.empty(need, dtype=torch.uint8, device=dev)
             ch["bwd"] = B.make_bwd_params(ch["fwd"], ch["d_o"], ch["d_q"], ch["dk"], ch["dv"],
-                                          self.workspaces[ch["lane"]])
+                                          ch.get("workspace", self.workspaces[ch["lane"]]))
+        if self.fused_launch:
+            self.fwd_batch = B.params_array([self.chunks[c]["fwd"] for c in self.forward_order()])
+            self.bwd_batch = B.params_array([self.chunks[c]["bwd"] for c in self.backward_order()])
         self.total_pairs = sum(ch["pairs"] for ch in self.chunks)
         return self
 
@@ -155,11 +164,18 @@ class ChunkAttention:
             done.record(st)
             cur.wait_event(done)
 
-    def run_forward(self):
-        self._launch((False, c) for c in self.forward_order())          # ascending inside each group
+    def run_forward(self, fused=None):
+        """fused: None = as constructed; True needs fused_launch=True at construction."""
+        if self.fused_launch if fused is None else fused:
+            B.cf_attn_fwd_batch(self.fwd_batch)
+        else:
+            self._launch((False, c) for c in self.forward_order())      # ascending inside each group
 
-    def run_backward(self):
-        self._launch((True, c) for c in self.backward_order())          # descending inside each group
+    def run_backward(self, fused=None):
+        if self.fused_launch if fused is None else fused:
+            B.cf_attn_bwd_batch(self.bwd_batch)
+        else:
+            self._launch((True, c) for c in self.backward_order())      # descending inside each group
 
     def run_schedule(self, K):
         """Algorithm 2 with K kept chunks: chunks marked FWD_DISCARD run forward (their K/V state is

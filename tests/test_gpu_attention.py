@@ -76,6 +76,25 @@ def test_recompute_schedule_gives_same_result():
             assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
 
 
+@pytest.mark.parametrize("dtype,D,lens,C,Hq,Hkv", [
+    ("bf16", 128, [1500, 40, 300, 77, 512, 129, 640, 9, 333, 200, 256, 31, 480, 64, 100, 700, 90, 411], 512, 8, 2),
+    ("bf16", 128, [900, 40, 300], 256, 4, 2),
+    ("fp32", 64, [700, 33, 1, 120, 64], 200, 2, 2),          # no MFMA path: the batch call falls back to single launches
+])
+def test_whole_plan_launch_matches_per_chunk_calls(dtype, D, lens, C, Hq, Hkv):
+    """cf_attn_fwd_batch / cf_attn_bwd_batch (forward and dQ kernels of many chunks as one launch, more chunks
+    than one launch holds in the first case) give what one call per chunk gives: O, LSE, dQ bit for bit, dK/dV
+    to the parity tolerance (the heads of a group meet through atomic adds in both)."""
+    a, _ = P.run_gpu(lens, C, Hq, Hkv, D, dtype, seed=7)
+    b, eng = P.run_gpu(lens, C, Hq, Hkv, D, dtype, seed=7, fused_launch=True)
+    assert eng.fused_launch and len(eng.chunks) >= 3
+    ref = P.run_oracle(lens, Hq, Hkv, D, dtype, seed=7)
+    print(len(eng.chunks), "chunks", P.check(b, ref, dtype, "whole-plan launch"))
+    for sid in a:
+        for n in ("o", "lse", "dq"):
+            assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
+
+
 def test_strided_views_and_nonzero_initial_grads():
     """q/k/v as views into one packed buffer; dK/dV must be added to, dQ overwritten."""
     torch.manual_seed(0)

@@ -153,3 +153,17 @@ def test_schedule_memory_is_bounded_by_k_times_chunk_size():
         m4 = schedule_memory(plan, 4, 28, 4, 128)
         assert m4["kept_activation_bytes"] <= 4 * m["kept_activation_bytes"] and m4["n_reforward"] < m["n_reforward"]
         plan.close()
+
+
+def test_batch_entry_points_reject_bad_arguments_without_a_gpu():
+    """Every chunk of a batch call is checked on the host before anything is enqueued."""
+    L = B.lib()
+    assert L.cf_attn_fwd_batch(None, 0, None) == B.CF_OK and L.cf_attn_bwd_batch(None, 0, None) == B.CF_OK
+    assert L.cf_attn_fwd_batch(None, 2, None) == B.CF_EINVAL and L.cf_attn_bwd_batch(None, -1, None) == B.CF_EINVAL
+    arr = (B.AttnFwdParams * 2)()
+    for p in arr:
+        p.dtype, p.head_dim, p.n_q_heads, p.n_kv_heads = B.CF_BF16, 128, 4, 2
+        p.n_tokens, p.n_kv_tokens, p.n_segments = 16, 16, 1
+    assert L.cf_attn_fwd_batch(arr, 2, None) == B.CF_EINVAL and b"NULL" in L.cf_last_error()
+    arr[1].head_dim = 96
+    assert L.cf_attn_fwd_batch(arr, 2, None) in (B.CF_EINVAL, B.CF_EUNSUPPORTED)
