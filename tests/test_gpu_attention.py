@@ -95,6 +95,21 @@ def test_whole_plan_launch_matches_per_chunk_calls(dtype, D, lens, C, Hq, Hkv):
             assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
 
 
+def test_groups_dealt_over_streams_give_the_same_result():
+    """The runner's multi-stream dispatch (groups on different streams, a workspace per stream, K = 1 schedule
+    included) changes nothing: O, LSE, dQ bit for bit, dK/dV to the parity tolerance."""
+    lens = [1500, 40, 300, 77, 512, 129, 640, 9, 333, 200, 256, 31, 480, 64]
+    a, _ = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=9)
+    ref = P.run_oracle(lens, 8, 2, 128, "bf16", seed=9)
+    for kw in (dict(n_streams=3), dict(n_streams=2, K=1)):
+        b, eng = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=9, **kw)
+        assert len(eng.streams) == kw["n_streams"] and len({ch["lane"] for ch in eng.chunks}) == kw["n_streams"]
+        P.check(b, ref, "bf16", f"streams {kw}")
+        for sid in a:
+            for n in ("o", "lse", "dq"):
+                assert np.array_equal(a[sid][n], b[sid][n]), (kw, sid, n)
+
+
 def test_strided_views_and_nonzero_initial_grads():
     """q/k/v as views into one packed buffer; dK/dV must be added to, dQ overwritten."""
     torch.manual_seed(0)
