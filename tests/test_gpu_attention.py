@@ -64,6 +64,19 @@ def test_edge_cases(flags):
         P.check(got, ref, "bf16", f"lens={lens} C={C}")
 
 
+@pytest.mark.parametrize("flags", [SCALAR, 0])
+def test_many_tiny_documents_in_one_chunk(flags):
+    """More than 64 documents in one chunk (the on-device tile search walks the segment list in groups of 64,
+    the dK/dV work list has one item per document) and more than 128: 300 documents of 1..40 tokens."""
+    rng = np.random.default_rng(12)
+    lens = [int(x) for x in rng.integers(1, 41, size=300)]
+    C = sum(lens[:150]) + 7                     # two or three packed chunks, each with far more than 64 documents
+    got, eng = P.run_gpu(lens, C, 4, 2, 128, "bf16", seed=6, flags=flags)
+    assert max(len(ch["segs"]) for ch in eng.chunks) > 128
+    ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=6)
+    P.check(got, ref, "bf16", "300 tiny documents")
+
+
 def test_recompute_schedule_gives_same_result():
     """Algorithm 2 with K=1: the first N-1 chunks run forward twice; results must not change."""
     lens = [900, 40, 300]
