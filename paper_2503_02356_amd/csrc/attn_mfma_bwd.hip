@@ -132,12 +132,12 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         seg = id;                                    // one head block per (segment, key/value head)
         if (seg >= p.n_segments) return;
     } else if (FUSED_HEADS) {
-        int t_rev;
-        if (!locate_tile(p.cu_seqlens_k, p.n_segments, BKV, id, seg, t_rev)) return;
+        TileLocation loc;
+        if (!locate_tile(p.cu_seqlens_k, p.cu_seqlens_q, p.n_segments, BKV, id, loc)) return;
+        seg = loc.seg;
         // locate_tile numbers tiles from the end; the FIRST key tiles of a segment are seen by the most rows, so
         // flip the order inside the segment to start the heaviest tiles first.
-        const int lk_ = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
-        kt0 = ((lk_ + BKV - 1) / BKV - 1 - t_rev) * BKV;
+        kt0 = ((loc.len + BKV - 1) / BKV - 1 - loc.tile_in_seg) * BKV;
     } else {
         const int n_first = wl[0], n_second = wl[1];
         if (id >= n_first + n_second) return;
@@ -490,15 +490,19 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     const int h = kh * G + id % G;
     const int rank = id / G;
 
-    int seg, tile_in_seg = 0;
+    int tile_in_seg = 0, q_seg0, lq, k_seg0, lk;
     if (HEAD_TILES) {
-        seg = rank;                                  // one block per (segment, head)
+        const int seg = rank;                        // one block per (segment, head)
         if (seg >= p.n_segments) return;
-    } else if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) {
-        return;
+        q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
+        k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
+    } else {
+        TileLocation loc;
+        if (!locate_tile(p.cu_seqlens_q, p.cu_seqlens_k, p.n_segments, BM, rank, loc)) return;
+        // (the same in every lane, but values that leave the search loop do not look that way to the compiler)
+        tile_in_seg = uniform(loc.tile_in_seg);
+        q_seg0 = uniform(loc.begin), lq = uniform(loc.len), k_seg0 = uniform(loc.other_begin), lk = uniform(loc.other_len);
     }
-    const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
-    const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
     const int off = lk - lq;
     const int q_tile0 = tile_in_seg * BM;
     // the tile whose rows sit among the first 128 positions of a sequence belongs to the head blocks

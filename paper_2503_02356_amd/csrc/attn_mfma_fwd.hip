@@ -37,10 +37,11 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
     const int h = kh * G + id % G;
     const int rank = id / G;
 
-    int seg, tile_in_seg;
-    if (!locate_tile(p.cu_seqlens_q, p.n_segments, BM, rank, seg, tile_in_seg)) return;
-    const int q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
-    const int k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
+    TileLocation loc;
+    if (!locate_tile(p.cu_seqlens_q, p.cu_seqlens_k, p.n_segments, BM, rank, loc)) return;
+    // (the same in every lane, but values that leave the search loop do not look that way to the compiler)
+    const int tile_in_seg = uniform(loc.tile_in_seg);
+    const int q_seg0 = uniform(loc.begin), lq = uniform(loc.len), k_seg0 = uniform(loc.other_begin), lk = uniform(loc.other_len);
     const int off = lk - lq;                         // prefix keys every row of the segment sees
     const int q_tile0 = tile_in_seg * BM;
     const int rows_valid = min(BM, lq - q_tile0);

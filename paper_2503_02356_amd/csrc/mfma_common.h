@@ -167,14 +167,28 @@ __device__ __forceinline__ float sum_with_other_half(float x)
 // and numbered from the LAST tile of the LAST segment backwards (the later tiles of a segment see more
 // keys, so the heaviest tiles get the lowest ranks and start first).  Every lane of every wavefront
 // computes the same answer.  Returns false if rank >= number of tiles.
-__device__ __forceinline__ bool locate_tile(const int32_t *cu, int n_seg, int tile, int rank, int &seg,
-                                            int &tile_in_seg)
+// The lanes that scan the segment list load its bounds in BOTH lists (cu: the list the tiles are counted
+// over, cu_other: the other one), and the winner's values are handed out by lane reads: the caller gets
+// the segment's four bounds without a second, dependent round of loads.
+struct TileLocation {
+    int seg, tile_in_seg;
+    int begin, len;               // of the segment in cu
+    int other_begin, other_len;   // of the segment in cu_other
+};
+__device__ __forceinline__ bool locate_tile(const int32_t *cu, const int32_t *cu_other, int n_seg, int tile, int rank,
+                                            TileLocation &out)
 {
     const int lane = threadIdx.x & 63;
     for (int base = 0; base < n_seg; base += 64) {
         const int gi = n_seg - 1 - (base + lane);
-        int cnt = 0;
-        if (gi >= 0) cnt = (cu[gi + 1] - cu[gi] + tile - 1) / tile;
+        int cnt = 0, b0 = 0, b1 = 0, o0 = 0, o1 = 0;
+        if (gi >= 0) {
+            b0 = cu[gi];
+            b1 = cu[gi + 1];
+            o0 = cu_other[gi];
+            o1 = cu_other[gi + 1];
+            cnt = (b1 - b0 + tile - 1) / tile;
+        }
         int inc = cnt;
         for (int o = 1; o < 64; o <<= 1) {
             const int t = __shfl_up(inc, o);
@@ -186,8 +200,12 @@ __device__ __forceinline__ bool locate_tile(const int32_t *cu, int n_seg, int ti
             const int first = __ffsll((long long)ball) - 1;
             const int exc = __shfl(inc - cnt, first);
             const int c = __shfl(cnt, first);
-            seg = __builtin_amdgcn_readfirstlane(n_seg - 1 - (base + first));
-            tile_in_seg = __builtin_amdgcn_readfirstlane(c - 1 - (rank - exc));
+            out.seg = __builtin_amdgcn_readfirstlane(n_seg - 1 - (base + first));
+            out.tile_in_seg = __builtin_amdgcn_readfirstlane(c - 1 - (rank - exc));
+            out.begin = __builtin_amdgcn_readfirstlane(__shfl(b0, first));
+            out.len = __builtin_amdgcn_readfirstlane(__shfl(b1 - b0, first));
+            out.other_begin = __builtin_amdgcn_readfirstlane(__shfl(o0, first));
+            out.other_len = __builtin_amdgcn_readfirstlane(__shfl(o1 - o0, first));
             return true;
         }
         rank -= total;
