@@ -635,18 +635,12 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     }
     sweep(std::false_type());
 
-    if (wave_active && iq < lq) {
-        const int row = q_seg0 + iq;
-        char *out = (char *)b.d_q + ((int64_t)row * b.dq_stride_tok + (int64_t)h * b.dq_stride_head) * 2;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(dq[j][g4 * 4 + e] * p.softmax_scale);
-                *(bf16x4 *)(out + (j * 32 + g4 * 8 + half * 4) * 2) = w;
-            }
+    if (wave_active) {
+        // dQ rows leave through this wavefront's part of the (now idle) stage buffers, whole rows per store instruction
+        char *scratch = (wave < 2 ? stage_a : stage_b) + (wave & 1) * kRowScratchBytes;
+        store_rows_bf16(dq, p.softmax_scale, scratch, lq - wq0, [&](int r) {
+            return (char *)b.d_q + ((int64_t)(q_seg0 + wq0 + r) * b.dq_stride_tok + (int64_t)h * b.dq_stride_head) * 2;
+        });
     }
 }
 

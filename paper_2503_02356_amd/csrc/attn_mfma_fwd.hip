@@ -161,22 +161,14 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
 
     if (!wave_active) return;
     const float l_tot = sum_with_other_half(l_run);
-    if (iq < lq) {
-        const float inv = 1.f / l_tot;
-        const int row = q_seg0 + iq;
-        char *orow = (char *)p.o + ((int64_t)row * p.o_stride_tok + (int64_t)h * p.o_stride_head) * 2;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-                bf16x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[j][g4 * 4 + e] * inv);
-                *(bf16x4 *)(orow + (j * 32 + g4 * 8 + half * 4) * 2) = w;
-            }
-        if (half == 0)
-            p.lse[(int64_t)h * p.n_tokens + row] = m_run * 0.69314718055994530942f + __logf(l_tot);
-    }
+    // O rows leave through this wavefront's part of the (now idle) stage buffers, whole rows per store instruction.
+    // The scale of a padding row (l_tot = 0 cannot happen: every real row sees its own key) is never stored.
+    char *scratch = (wave < 2 ? stage_a : stage_b) + (wave & 1) * kRowScratchBytes;
+    store_rows_bf16(o_acc, 1.f / l_tot, scratch, lq - wq0, [&](int r) {
+        return (char *)p.o + ((int64_t)(q_seg0 + wq0 + r) * p.o_stride_tok + (int64_t)h * p.o_stride_head) * 2;
+    });
+    if (iq < lq && half == 0)
+        p.lse[(int64_t)h * p.n_tokens + q_seg0 + iq] = m_run * 0.69314718055994530942f + __logf(l_tot);
 }
 
 __global__ __launch_bounds__(256, 2) void mfma_fwd_kernel(cf_attn_fwd_params p)

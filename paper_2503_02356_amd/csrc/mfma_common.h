@@ -149,6 +149,39 @@ __device__ __forceinline__ T *uniform(T *p)
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
+// Stores a wavefront's 32 x 128 block of bf16 results (computed transposed: a lane owns one ROW, register group
+// (j, g4) of acc holds its 4 consecutive d starting at 32*j + 8*g4 + 4*half) to global rows of 256 bytes.
+// A direct store would write 8-byte pieces of 32 different rows per instruction (64 cache lines touched per
+// instruction, 16 instructions); instead the block is turned around in `scratch` (this wavefront's own
+// 32 x 272 bytes of LDS, free at that point) and leaves as 8 instructions that each write 4 whole rows.
+//   row_ptr(r): global address of row r of the block (r = 0..31), rows >= rows_valid are not written
+constexpr int kRowScratchStride = 272;          // 256 + 16: keeps 16-byte alignment, spreads rows over banks
+constexpr int kRowScratchBytes = 32 * kRowScratchStride;
+template <typename RowPtr>
+__device__ __forceinline__ void store_rows_bf16(const f32x16 (&acc)[4], float scale, char *scratch, int rows_valid,
+                                                RowPtr row_ptr)
+{
+    const int lane = threadIdx.x & 63, half = lane >> 5, col = lane & 31;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(acc[j][g4 * 4 + e] * scale);
+            *(bf16x4 *)(scratch + col * kRowScratchStride + (j * 32 + g4 * 8 + half * 4) * 2) = w;
+        }
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = *(const bf16x8 *)(scratch + (4 * i + (lane >> 4)) * kRowScratchStride + (lane & 15) * 16);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        if (r < rows_valid) *(bf16x8 *)(row_ptr(r) + (lane & 15) * 16) = v[i];
+    }
+}
+
 // Lane l and lane l ^ 32 combine a value without going through LDS: v_permlane32_swap with both operands = x
 // returns (x of the lower half, x of the upper half) in every lane (checked on the device with a probe).
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
