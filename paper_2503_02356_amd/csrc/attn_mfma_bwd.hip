@@ -580,6 +580,9 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 
             if (wave_active && tile_start < wave_kmax) {
                 const bool need_mask = tile_start + BN - 1 > wq0 + off;
+                // register i of block mb is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4: masked iff the
+                // compile-time part of that exceeds lim
+                const int lim = amax - tile_start - half * 4;
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
                     // S^T and dP^T for 32 keys: register i is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4
@@ -595,7 +598,7 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
-                        if (need_mask && tile_start + mb * 32 + (i >> 2) * 8 + half * 4 + (i & 3) > amax) pv = 0.f;
+                        if (need_mask && mb * 32 + (i >> 2) * 8 + (i & 3) > lim) pv = 0.f;
                         if (DELTA_PASS) dsum += pv * dp[i];
                         else dp[i] = pv * (dp[i] - dlt);
                     }

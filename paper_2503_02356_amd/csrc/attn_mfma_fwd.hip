@@ -103,13 +103,14 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
             }
             // ---- causal mask, only on tiles that cross this wavefront's diagonal
             if (tile_start + BN - 1 > wq0 + off) {
+                // register i of block mb is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4: masked iff the
+                // compile-time part of that exceeds lim (one compare with a constant + one select per element)
+                const int lim = amax - tile_start - half * 4;
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int key = tile_start + mb * 32 + (i >> 2) * 8 + half * 4 + (i & 3);
-                        if (key > amax) s[mb][i] = -INFINITY;
-                    }
+                    for (int i = 0; i < 16; ++i)
+                        if (mb * 32 + (i >> 2) * 8 + (i & 3) > lim) s[mb][i] = -INFINITY;
             }
             // ---- online softmax (log2 domain)
             float mx = s[0][0];
