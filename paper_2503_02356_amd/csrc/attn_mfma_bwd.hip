@@ -62,7 +62,9 @@ static_assert(DKV_STAGE_BYTES >= 4 * 2 * EXCH_SLOT_BYTES, "exchange area too sma
 // is int4 {segment, kt0, g0, n_heads}.
 constexpr int kSplitTarget = 48;
 
-__global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
+// Runs in ONE workgroup of any size: as a kernel of its own (whole-plan launches) or as the last workgroup of the dQ
+// launch, which the dK/dV kernel follows anyway (no launch of its own on the per-chunk path).
+__device__ __forceinline__ void build_dkv_worklist(const cf_attn_fwd_params &p, int *wl, int capacity)
 {
     __shared__ int n_first, n_second;
     if (threadIdx.x == 0) n_first = n_second = 0;
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p
         const int lk = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
         const int off = lk - lq;
         const int n_head_qt = off < 128 ? min((lq + 63) / 64, (128 - off + 63) / 64) : 0;
-        for (int kt0 = threadIdx.x * 128; kt0 < lk; kt0 += 1024 * 128) {
+        for (int kt0 = threadIdx.x * 128; kt0 < lk; kt0 += (int)blockDim.x * 128) {
             const int qt_first = kt0 == 0 ? n_head_qt : max(0, kt0 - off) / 64;
             const int n_qt = (lq + 63) / 64 - qt_first;
             if (n_qt <= 0) continue;
@@ -95,6 +97,10 @@ __global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p
         wl[0] = n_first;
         wl[1] = n_second;
     }
+}
+__global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
+{
+    build_dkv_worklist(p, wl, capacity);
 }
 
 // HEAD_TILES = false: a main block.  It leaves out the tile pairs made of a sequence's first 128
@@ -648,8 +654,14 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 }
 
 // Blocks [0, head_blocks) do the head tiles (one per (segment, head)), the others the main work.
-__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, float *__restrict__ delta, int head_blocks)
+// wl != nullptr: the launch has one extra workgroup (the last) that builds the dK/dV work list.
+__global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, float *__restrict__ delta, int head_blocks,
+                                                         int *wl, int capacity)
 {
+    if (wl != nullptr && blockIdx.x == gridDim.x - 1) {
+        build_dkv_worklist(b.f, wl, capacity);
+        return;
+    }
     // Two separate arrays (not one array with two halves): the compiler must see that the direct-to-LDS
     // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
     __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
@@ -743,10 +755,11 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     const BwdShape g = bwd_shape(p, ws);
     if (!g.ok) return hipErrorInvalidConfiguration;
     hipError_t e;
-    if ((e = launch_worklist(p, ws, g, s)) != hipSuccess) return e;
     // dQ first: it also produces delta (main blocks: <dO, O>; head blocks: the exact sum for the head rows), which
-    // the dK/dV kernel reads.
-    mfma_dq_kernel<<<dim3((unsigned)(g.dq_blocks + g.head_dq)), 256, 0, s>>>(b, ws.delta, g.head_dq);
+    // the dK/dV kernel reads; its last workgroup builds the dK/dV work list where one is needed.
+    int *wl = g.fused ? nullptr : ws.worklist;
+    mfma_dq_kernel<<<dim3((unsigned)(g.dq_blocks + g.head_dq + (wl ? 1 : 0))), 256, 0, s>>>(b, ws.delta, g.head_dq, wl,
+                                                                                             (int)ws.worklist_items);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     return launch_dkv(b, ws, g, take_profile_hook(), s);
 }
