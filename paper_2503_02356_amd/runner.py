@@ -59,6 +59,18 @@ class ChunkAttention:
             sid = int(p.seg_seq_id[s])
             seq_len[sid] = max(seq_len.get(sid, 0), int(p.seg_seq_start[s]) + int(p.seg_len[s]))
         ws_bytes = 0
+        # All fp32 dK/dV buffers (per long sequence, per packed chunk) are slices of ONE allocation, so that zeroing
+        # the gradients of a step is one fill.
+        row = self.Hkv * self.D
+        self.grad_arena = torch.zeros(2 * int(p.total_tokens) * row, dtype=torch.float32, device=dev)
+        self._grad_used = 0
+
+        def grad_pair(n_rows):
+            a = self._grad_used
+            self._grad_used += 2 * n_rows * row
+            dk = self.grad_arena[a:a + n_rows * row].view(n_rows, self.Hkv, self.D)
+            dv = self.grad_arena[a + n_rows * row:a + 2 * n_rows * row].view(n_rows, self.Hkv, self.D)
+            return dk, dv
         for c in range(p.n_chunks):
             segs = p.chunk_segments(c)
             T, P = int(p.chunk_tokens[c]), int(p.chunk_prefix_len[c])
@@ -78,9 +90,8 @@ class ChunkAttention:
                 L = seq_len[sid]
                 vals = get(sid, L)
                 if g not in self.state:
-                    self.state[g] = {"k": up(vals["k"]), "v": up(vals["v"]),
-                                     "dk": torch.zeros((L, self.Hkv, self.D), dtype=torch.float32, device=dev),
-                                     "dv": torch.zeros((L, self.Hkv, self.D), dtype=torch.float32, device=dev)}
+                    gdk, gdv = grad_pair(L)
+                    self.state[g] = {"k": up(vals["k"]), "v": up(vals["v"]), "dk": gdk, "dv": gdv}
                 st = self.state[g]
                 ch["k"], ch["v"] = st["k"][:P + T], st["v"][:P + T]
                 ch["dk"], ch["dv"] = st["dk"][:P + T], st["dv"][:P + T]
@@ -90,8 +101,7 @@ class ChunkAttention:
             else:
                 ch["k"] = torch.empty((T, self.Hkv, self.D), dtype=dt, device=dev)
                 ch["v"] = torch.empty_like(ch["k"])
-                ch["dk"] = torch.zeros((T, self.Hkv, self.D), dtype=torch.float32, device=dev)
-                ch["dv"] = torch.zeros_like(ch["dk"])
+                ch["dk"], ch["dv"] = grad_pair(T)
                 for i, (sid, start, n) in enumerate(segs):
                     vals = get(sid, n)
                     a, b = int(cu[i]), int(cu[i + 1])
@@ -130,11 +140,7 @@ class ChunkAttention:
 
     # ------------------------------------------------------------------ launches
     def zero_grads(self):
-        for st in self.state.values():
-            st["dk"].zero_(); st["dv"].zero_()
-        for ch in self.chunks:
-            if not ch["dependent"]:
-                ch["dk"].zero_(); ch["dv"].zero_()
+        self.grad_arena.zero_()
 
     def forward_order(self):
         return [c for g in range(self.plan.n_groups) for c in self.plan.group(g)]
