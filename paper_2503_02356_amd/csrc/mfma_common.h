@@ -100,13 +100,17 @@ __device__ __forceinline__ LaneOffsets lane_offsets()
 __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Direct global -> LDS copy of a swizzled tile of ROWS x 256 bytes by a workgroup of WAVES wavefronts
-// (global_load_lds_dwordx4: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
+// (buffer_load_dwordx4 ... lds: no staging registers; lane i of one instruction lands at LDS base + 16*i, so
 // one instruction fills 4 tile rows and the swizzle is applied on the global side: the lane that fills
 // physical unit u' of row r fetches logical unit u' ^ swz(r)).
 // A tile takes ROWS / (4 * WAVES) instructions per wavefront (PARTS); each costs the issuing wavefront some 30-45 clocks
 // wherever it is placed (measured), so they are simply issued together at the start of a tile.
-// Per tile the source is a wave-uniform pointer to logical row 0 (scalar address arithmetic); rows beyond
-// last_row (relative to src) re-read last_row (the caller masks them).
+// Addressing is the buffer form on purpose: the tile's first row is a wave-uniform pointer that becomes the
+// base of a buffer descriptor (scalar arithmetic), the lane's place inside a tile is ONE register computed
+// at init, and a part adds a scalar offset, so a full tile costs no vector address arithmetic at all.  Only
+// a ragged tile (rows beyond last_row, relative to src, re-read last_row; the caller masks them) computes
+// clamped per-lane offsets.  The descriptor's size field is left at its maximum: nothing relies on the
+// hardware's out-of-range behaviour.
 // Completion is tracked by vmcnt: wait_lds_dma() before the barrier that publishes the tile.
 template <int ROWS, int WAVES = 4>
 struct TileDma {
@@ -115,6 +119,7 @@ struct TileDma {
     unsigned row_bytes, unit16;   // unit16: byte offset of this lane's 16-byte unit inside its row (same for all parts)
     int r0;                       // this lane's row in part 0; part c adds 4 * WAVES rows
     int wv;                       // index of this wavefront among the copying ones
+    unsigned lane_off;            // r0 * row_bytes + unit16: this lane's offset in part 0 of a full tile
 
     // wave: index of the calling wavefront among the WAVES that copy (wave-uniform)
     __device__ __forceinline__ void init(int64_t row_bytes_, int wave)
@@ -124,18 +129,39 @@ struct TileDma {
         wv = wave;
         r0 = 4 * wave + (lane >> 4);
         unit16 = ((lane & 15) ^ swz(r0)) * 16;       // swz() has period 16 rows
+        lane_off = (unsigned)r0 * row_bytes + unit16;
     }
     __device__ __forceinline__ void init(int64_t row_bytes_) { init(row_bytes_, wave_id()); }
+    __device__ __forceinline__ CF_LDS void *part_dst(char *lds_tile, int c) const { return (CF_LDS void *)(lds_tile + (c * WAVES + wv) * 1024); }
+    __device__ __forceinline__ static __amdgpu_buffer_rsrc_t descriptor(const char *src)
+    {
+        return __builtin_amdgcn_make_buffer_rsrc((void *)src, 0, -1, 0x00020000);
+    }
+    __device__ __forceinline__ void full_part(__amdgpu_buffer_rsrc_t rsrc, char *lds_tile, int c) const
+    {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, part_dst(lds_tile, c), 16, (int)lane_off, (int)(4 * WAVES * c * row_bytes), 0, 0);
+    }
+    __device__ __forceinline__ void ragged_part(__amdgpu_buffer_rsrc_t rsrc, int last_row, char *lds_tile, int c) const
+    {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, part_dst(lds_tile, c), 16,
+                                                 (int)((unsigned)min(r0 + 4 * WAVES * c, last_row) * row_bytes + unit16), 0, 0, 0);
+    }
+    // last_row is wave-uniform, so the branches below are scalar ones.
     __device__ __forceinline__ void issue_part(const char *src, int last_row, char *lds_tile, int c) const
     {
-        const char *g = src + ((unsigned)min(r0 + 4 * WAVES * c, last_row) * row_bytes + unit16);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)g,
-                                         (CF_LDS void *)(lds_tile + (c * WAVES + wv) * 1024), 16, 0, 0);
+        if (last_row >= ROWS - 1) full_part(descriptor(src), lds_tile, c);
+        else ragged_part(descriptor(src), last_row, lds_tile, c);
     }
     __device__ __forceinline__ void issue(const char *src, int last_row, char *lds_tile) const
     {
+        const __amdgpu_buffer_rsrc_t rsrc = descriptor(src);
+        if (last_row >= ROWS - 1) {
 #pragma unroll
-        for (int c = 0; c < PARTS; ++c) issue_part(src, last_row, lds_tile, c);
+            for (int c = 0; c < PARTS; ++c) full_part(rsrc, lds_tile, c);
+        } else {
+#pragma unroll
+            for (int c = 0; c < PARTS; ++c) ragged_part(rsrc, last_row, lds_tile, c);
+        }
     }
 };
 // Makes a pointer / an int that is the same in every lane known as such to the compiler.
