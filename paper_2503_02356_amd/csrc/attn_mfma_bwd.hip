@@ -592,15 +592,35 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb) {
                     // S^T and dP^T for 32 keys: register i is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4
+                    // All 16 fragments are requested before the first MFMA: the LDS latency is paid once per
+                    // block, not once per MFMA.
                     f32x16 s, dp;
+                    bf16x8 ka[8], va[8];
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        ka[ks] = lds_read_b128(ks_ + mb * 8192 + lo.row_unit[ks]);
+                        va[ks] = lds_read_b128(vs_ + mb * 8192 + lo.row_unit[ks]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int j = 0; j < 16; ++j) s[j] = dp[j] = 0.f;
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        s = mfma32(lds_read_b128(ks_ + mb * 8192 + lo.row_unit[ks]), qf[ks], s);
+                    for (int ks = 0; ks < 8; ++ks) {
+                        s = mfma32(ka[ks], qf[ks], s);
+                        dp = mfma32(va[ks], dof[ks], dp);
+                    }
+                    // K^T fragments of the dQ contraction: requested now, so that they arrive during the arithmetic
+                    bf16x8 kt[2][4];
+                    if (!DELTA_PASS) {
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        dp = mfma32(lds_read_b128(vs_ + mb * 8192 + lo.row_unit[ks]), dof[ks], dp);
+                        for (int tq = 0; tq < 2; ++tq)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const char *ka_ = ks_ + mb * 8192 + tq * 4096;
+                                kt[tq][j] = lds_read_tr_pair(ka_ + lo.tr_lo[j], ka_ + lo.tr_hi[j]);
+                            }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
@@ -614,17 +634,14 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
                     for (int tq = 0; tq < 2; ++tq) {
                         const bf16x8 dsb = pack8(dp[8 * tq + 0], dp[8 * tq + 1], dp[8 * tq + 2], dp[8 * tq + 3],
                                                  dp[8 * tq + 4], dp[8 * tq + 5], dp[8 * tq + 6], dp[8 * tq + 7]);
-                        const char *ka = ks_ + mb * 8192 + tq * 4096;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dsb, dq[j]);
+                        for (int j = 0; j < 4; ++j) dq[j] = mfma32(kt[tq][j], dsb, dq[j]);
                         if (HEAD_TILES) {   // add the bf16 rounding residual of dS
                             bf16x8 dl;
 #pragma unroll
                             for (int e = 0; e < 8; ++e) dl[e] = (__bf16)(dp[8 * tq + e] - (float)dsb[e]);
 #pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                dq[j] = mfma32(lds_read_tr_pair(ka + lo.tr_lo[j], ka + lo.tr_hi[j]), dl, dq[j]);
+                            for (int j = 0; j < 4; ++j) dq[j] = mfma32(kt[tq][j], dl, dq[j]);
                         }
                     }
                 }

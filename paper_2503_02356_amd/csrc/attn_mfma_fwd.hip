@@ -92,15 +92,23 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
 
         if (wave_active && tile_start < wave_kmax) {
             // ---- S^T = K Q^T : two 32-key blocks
+            // All 16 K fragments are requested before the first MFMA: the LDS latency is paid once per tile,
+            // not once per MFMA (the matrix unit then consumes them in arrival order).
             f32x16 s[2];
+            bf16x8 ka[2][8];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) ka[mb][ks] = lds_read_b128(stage + mb * 8192 + lo.row_unit[ks]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                 for (int j = 0; j < 16; ++j) s[mb][j] = 0.f;
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    s[mb] = mfma32(lds_read_b128(stage + mb * 8192 + lo.row_unit[ks]), qf[ks], s[mb]);
-            }
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) s[mb] = mfma32(ka[mb][ks], qf[ks], s[mb]);
             // ---- causal mask, only on tiles that cross this wavefront's diagonal
             if (tile_start + BN - 1 > wq0 + off) {
                 // register i of block mb is key tile_start + 32*mb + (i/4)*8 + 4*half + i%4: masked iff the
