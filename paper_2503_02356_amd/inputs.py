@@ -92,3 +92,17 @@ def seq_values(seed, seq_id, L, Hq, Hkv, D, dtype):
         x = rng.standard_normal((int(L), H, D), dtype=np.float32)
         out[name] = round_to_bf16(x) if dtype == "bf16" else x
     return out
+
+
+def seq_values_device(seed, seq_id, L, Hq, Hkv, D, dtype, device):
+    """The same recipe drawn on the device by torch's seeded generator, for sizes where the host generator
+    takes minutes (a 262144-token sequence of 64 heads is 19 GB of fp32): q, k, v, d_o as torch tensors in
+    the storage dtype.  (A different stream than seq_values: the two are not interchangeable.)"""
+    import torch
+    out = {}
+    for t, (name, H) in enumerate((("q", Hq), ("k", Hkv), ("v", Hkv), ("d_o", Hq))):
+        g = torch.Generator(device=device)
+        g.manual_seed((int(seed) * 1000003 + int(seq_id)) * 4 + t)
+        x = torch.randn((int(L), H, D), generator=g, device=device, dtype=torch.float32)
+        out[name] = x.to(torch.bfloat16) if dtype == "bf16" else x
+    return out

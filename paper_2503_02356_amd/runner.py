@@ -43,10 +43,10 @@ class ChunkAttention:
 
     # ------------------------------------------------------------------ data placement
     def load(self, values):
-        """values(seq_id, L) -> dict(q,k,v,d_o) of fp32 numpy arrays [L,H,D] (already representable
-        in the compute dtype)."""
+        """values(seq_id, L) -> dict(q,k,v,d_o) of fp32 numpy arrays or torch tensors [L,H,D] (already
+        representable in the compute dtype)."""
         p, dev, dt = self.plan, self.dev, self.tdtype
-        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt)
+        up = lambda a: (a if torch.is_tensor(a) else torch.from_numpy(np.ascontiguousarray(a))).to(dev).to(dt)
         cache = {}
 
         def get(sid, L):

@@ -1,8 +1,8 @@
-"""GPU parity at the FULL sizes of configs 2 and 3, in the launch configuration bench.py times (one
+"""GPU parity at the FULL sizes of configs 2, 3 and 5, in the launch configuration bench.py times (one
 cf_attn_fwd / cf_attn_bwd call per chunk through the plan runner).  The fp64 oracle cannot redo these
 sizes whole, so it recomputes sampled outputs one by one:
   - whole short sequences (all five tensors),
-  - single query rows of the 32768-token sequence (O, LSE, dQ; each needs only the keys before it),
+  - single query rows of the long (32768- / 262144-token) sequence (O, LSE, dQ; each needs only the keys before it),
   - dK/dV of the last keys of that sequence (they only depend on the last query rows).
 """
 import numpy as np
@@ -16,12 +16,25 @@ from paper_2503_02356_amd.runner import ChunkAttention
 from tests import parity as P
 
 pytestmark = pytest.mark.gpu
-HQ, HKV, D = 28, 4, 128
+D = 128
 SCALE = np.float32(1.0 / np.sqrt(D))
 f64 = lambda t: t.detach().to(torch.float64).cpu().numpy()
 
 
-def run_full(cfg, seed):
+def host_values(cfg, seed, lens):
+    HQ, HKV = inputs.CONFIGS[cfg]["Hq"], inputs.CONFIGS[cfg]["Hkv"]
+    return lambda sid: inputs.seq_values(seed, sid, lens[sid], HQ, HKV, D, "bf16")
+
+
+def device_values(cfg, seed, lens):
+    """fp32 numpy views of values drawn on the device (the host generator needs minutes for config 5)."""
+    HQ, HKV = inputs.CONFIGS[cfg]["Hq"], inputs.CONFIGS[cfg]["Hkv"]
+    return lambda sid: inputs.seq_values_device(seed, sid, lens[sid], HQ, HKV, D, "bf16", "cuda:0")
+
+
+def run_full(cfg, seed, on_device=False):
+    HQ, HKV = inputs.CONFIGS[cfg]["Hq"], inputs.CONFIGS[cfg]["Hkv"]
+
     def count(lens, C):
         p = B.cf_build_chunks(lens, C)
         n = p.n_chunks
@@ -30,17 +43,23 @@ def run_full(cfg, seed):
     lens, C = inputs.seq_lens(cfg, seed, count)
     lens = [int(x) for x in lens]
     plan = B.cf_build_chunks(lens, C)
-    vals = lambda sid, L: inputs.seq_values(seed, sid, lens[sid], HQ, HKV, D, "bf16")
-    eng = ChunkAttention(plan, HQ, HKV, D, "bf16").load(vals)
+    values = (device_values if on_device else host_values)(cfg, seed, lens)
+    eng = ChunkAttention(plan, HQ, HKV, D, "bf16").load(lambda sid, L: values(sid))
     eng.zero_grads()
     eng.run_forward()
     eng.run_backward()
     torch.cuda.synchronize()
-    return lens, C, plan, eng
+    return lens, C, plan, eng, values
 
 
-def check_short_sequences(lens, plan, eng, seed, picks):
+def host(x):
+    """fp32 numpy array of a generated tensor (numpy from the host generator, bf16 torch from the device one)."""
+    return x.float().cpu().numpy() if torch.is_tensor(x) else x
+
+
+def check_short_sequences(lens, plan, eng, values, picks):
     """All five tensors of whole short sequences against unsplit oracle attention."""
+    HQ, HKV = eng.Hq, eng.Hkv
     where = {}
     for c, ch in enumerate(eng.chunks):
         if not ch["dependent"]:
@@ -49,7 +68,7 @@ def check_short_sequences(lens, plan, eng, seed, picks):
     for sid in picks:
         c, a, n = where[sid]
         ch = eng.chunks[c]
-        v = inputs.seq_values(seed, sid, lens[sid], HQ, HKV, D, "bf16")
+        v = {k: host(x) for k, x in values(sid).items()}
         o, lse = OA.seq_attn_fwd(v["q"], v["k"], v["v"], SCALE)
         dq, dk, dv = OA.seq_attn_bwd(v["q"], v["k"], v["v"], o, lse, v["d_o"], SCALE)
         got = {0: dict(o=f64(ch["o"][a:a + n]), lse=f64(ch["lse"][:, a:a + n]), dq=f64(ch["d_q"][a:a + n]),
@@ -59,30 +78,36 @@ def check_short_sequences(lens, plan, eng, seed, picks):
 
 
 def test_config2_full_size_sampled_sequences():
-    lens, C, plan, eng = run_full("packed_8k", 0)
+    lens, C, plan, eng, values = run_full("packed_8k", 0)
     assert plan.n_chunks == 16 and C == 8192
     order = np.argsort(lens)
     picks = [int(order[0]), int(order[len(order) // 4]), int(order[len(order) // 2]), int(order[-8])]
-    check_short_sequences(lens, plan, eng, 0, picks)
+    check_short_sequences(lens, plan, eng, values, picks)
 
 
-def test_config3_full_size_sampled_rows_and_tail_keys():
-    lens, C, plan, eng = run_full("long32k_mixed", 0)
-    assert plan.n_chunks == 12 and lens[0] == 32768
+def check_long_sequence(lens, C, eng, values, rows, W):
+    """Sampled query rows (O, LSE, dQ) and the dK/dV of the last W keys of sequence 0, the long one."""
+    HQ, HKV = eng.Hq, eng.Hkv
     L = lens[0]
-    v = inputs.seq_values(0, 0, L, HQ, HKV, D, "bf16")
+    dev = values(0)
+    # the oracle needs every key and value, but only the sampled rows of q and d_o
+    v = {"k": host(dev["k"]), "v": host(dev["v"])}
+    take = sorted(set(rows) | set(range(L - W, L)))
+    at = {r: n for n, r in enumerate(take)}
+    idx = take if not torch.is_tensor(dev["q"]) else torch.tensor(take, device=dev["q"].device)
+    q_s, do_s = host(dev["q"][idx]), host(dev["d_o"][idx])
+    del dev
     g = eng.chunks[0]["group"]
-    # ---- single query rows (chunk boundaries, tile edges, the very last row)
-    rows = [0, 1, 127, 8191, 8192, 8193, 16383 + 64, 24576, 24576 + 4095, L - 1]
     got = {"o": [], "lse": [], "dq": []}
     ref = {"o": [], "lse": [], "dq": []}
     for r in rows:
         c, i = r // C, r % C
         ch = eng.chunks[c]
         assert ch["dependent"] and ch["P"] == c * C
-        o, lse = OA.chunk_attn_fwd(v["q"][r:r + 1], v["k"][:r + 1], v["v"][:r + 1], [0, 1], [0, r + 1], SCALE)
+        n = at[r]
+        o, lse = OA.chunk_attn_fwd(q_s[n:n + 1], v["k"][:r + 1], v["v"][:r + 1], [0, 1], [0, r + 1], SCALE)
         dk = np.zeros((r + 1, HKV, D)); dv = np.zeros((r + 1, HKV, D))
-        dq = OA.chunk_attn_bwd(v["q"][r:r + 1], v["k"][:r + 1], v["v"][:r + 1], o, lse, v["d_o"][r:r + 1],
+        dq = OA.chunk_attn_bwd(q_s[n:n + 1], v["k"][:r + 1], v["v"][:r + 1], o, lse, do_s[n:n + 1],
                                [0, 1], [0, r + 1], SCALE, dk, dv)
         ref["o"].append(o); ref["lse"].append(lse); ref["dq"].append(dq)
         got["o"].append(f64(ch["o"][i:i + 1])); got["lse"].append(f64(ch["lse"][:, i:i + 1])); got["dq"].append(f64(ch["d_q"][i:i + 1]))
@@ -93,8 +118,7 @@ def test_config3_full_size_sampled_rows_and_tail_keys():
         print(f"rows {name}: max-abs {err:.2e} rel-L2 {r2:.2e}", flush=True)
         assert err <= max_abs and r2 <= rel, (name, err, r2)
     # ---- dK/dV of the last W keys: complete once the last W query rows (all in the last chunk) are done
-    W = 160
-    qs, dos = v["q"][L - W:], v["d_o"][L - W:]
+    qs, dos = q_s[at[L - W]:], do_s[at[L - W]:]
     o, lse = OA.chunk_attn_fwd(qs, v["k"], v["v"], [0, W], [0, L], SCALE)
     dk = np.zeros((L, HKV, D)); dv = np.zeros((L, HKV, D))
     OA.chunk_attn_bwd(qs, v["k"], v["v"], o, lse, dos, [0, W], [0, L], SCALE, dk, dv)
@@ -104,6 +128,24 @@ def test_config3_full_size_sampled_rows_and_tail_keys():
         err, r2 = np.abs(a - b).max(), np.linalg.norm(a - b) / np.linalg.norm(b)
         print(f"tail keys {name}: max-abs {err:.2e} rel-L2 {r2:.2e}", flush=True)
         assert err <= max_abs and r2 <= rel, (name, err, r2)
+
+
+def test_config3_full_size_sampled_rows_and_tail_keys():
+    lens, C, plan, eng, values = run_full("long32k_mixed", 0)
+    assert plan.n_chunks == 12 and lens[0] == 32768
+    L = lens[0]
+    # single query rows: chunk boundaries, tile edges, the very last row
+    check_long_sequence(lens, C, eng, values, [0, 1, 127, 8191, 8192, 8193, 16383 + 64, 24576, 24576 + 4095, L - 1], 160)
     # ---- and a few of the packed short sequences of the same batch
     order = np.argsort(lens[1:]) + 1
-    check_short_sequences(lens, plan, eng, 0, [int(order[1]), int(order[len(order) // 2])])
+    check_short_sequences(lens, plan, eng, values, [int(order[1]), int(order[len(order) // 2])])
+
+
+def test_config5_full_size_sampled_rows_and_tail_keys():
+    """One 262144-token sequence in 8 chunks of 32768 (prefix state up to 229376 rows), 64 / 8 heads."""
+    lens, C, plan, eng, values = run_full("long256k_32k", 0, on_device=True)
+    assert plan.n_chunks == 12 and lens[0] == 262144 and C == 32768
+    L = lens[0]
+    check_long_sequence(lens, C, eng, values, [0, 32767, 32768, 131072 + 63, 229376, 229376 + 12345, L - 1], 32)
+    order = np.argsort(lens[1:]) + 1
+    check_short_sequences(lens, plan, eng, values, [int(order[1]), int(order[len(order) // 2])])
