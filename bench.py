@@ -18,12 +18,13 @@ PEAK_BF16_TFLOPS = 2516.6          # 256 CU x 4096 bf16 FLOP/clk/CU x 2.4 GHz (d
 WORKLOADS = {                       # name -> inputs.CONFIGS key
     "config2_packed_8k": "packed_8k",
     "config3_long32k_mixed": "long32k_mixed",
+    "config5_long256k_32k": "long256k_32k",   # values drawn on the device (the host generator needs minutes here)
 }
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (profiles/bench_<workload>_kernels.txt): FETCH_SIZE x 2.0 KiB + WRITE_SIZE x 1.0 KiB, the factors being
 # what the same counters read for the 512 MiB copy kernel below.  A measured constant of the build the profile was
 # taken on, not something this run re-measures.
-MEASURED_TRAFFIC_BYTES = {"config2_packed_8k": 521e6, "config3_long32k_mixed": 983e6}
+MEASURED_TRAFFIC_BYTES = {"config2_packed_8k": 521e6, "config3_long32k_mixed": 983e6, "config5_long256k_32k": None}
 
 
 def cpu_baseline(lens, cfg, seed, budget_pairs):
@@ -88,7 +89,10 @@ def main():
     t0 = time.perf_counter()
     plan = B.cf_build_chunks(lens, C)
     plan_ms = (time.perf_counter() - t0) * 1e3
-    vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
+    if cfg_key == "long256k_32k":
+        vals = lambda sid, L: inputs.seq_values_device(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"], "cuda:0")
+    else:
+        vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
     eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams, fused_launch=True).load(vals)
     pairs = eng.total_pairs
     flop_step = 14.0 * D * Hq * pairs
