@@ -61,6 +61,24 @@ typedef struct cf_plan cf_plan; /* opaque; owned by the caller after a successfu
  * < 1 -> CF_EINVAL and *out is untouched.  n_seqs == 0 gives a valid empty plan.
  */
 int cf_build_chunks(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size, cf_plan **out);
+
+/*
+ * Algorithm 1 with options (flags = 0: exactly cf_build_chunks).
+ *   CF_PLAN_MERGE_TAILS  A variant section 4.1 leaves open: the last slice of a split sequence, when shorter
+ *     than chunk_size, is not a chunk of its own but one more item of the bin-packing (its weight is its
+ *     length), so that it shares a chunk with short sequences instead of leaving that chunk mostly empty.
+ *     Items (short sequences and tails) are placed longest first (ties: sequence order) into the
+ *     least-loaded bin (ties: lowest bin); a tail only goes to a bin that holds no tail yet, so a chunk
+ *     depends on at most one split sequence.  An attempt fails when an item does not fit or a tail finds no
+ *     tail-free bin; the first BinCnt (1, 2, ...) that succeeds wins.
+ *     The chunk that holds a tail is the LAST chunk of that sequence's group (chunk_group, chunk_idx_in_group
+ *     say so; group_chunks lists it after the slices); its chunk_prefix_len is the tail's seg_seq_start and
+ *     its segments are in sequence order like any packed chunk.  Only the tail segment has seg_seq_start > 0:
+ *     for the kernels that is a chunk with one segment whose keys are longer than its queries.
+ * Errors as cf_build_chunks; unknown flag bits -> CF_EINVAL.
+ */
+enum { CF_PLAN_MERGE_TAILS = 1 };
+int cf_build_chunks_ex(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size, uint32_t flags, cf_plan **out);
 void cf_plan_free(cf_plan *plan); /* NULL is fine */
 
 /* Read-only view of a plan.  All pointers are host memory borrowed from the plan and stay valid
@@ -69,7 +87,8 @@ typedef struct {
     int64_t n_chunks, n_segments, n_groups, total_tokens, chunk_size;
     const int64_t *chunk_seg_ptr;      /* [n_chunks+1]                                          */
     const int32_t *chunk_tokens;       /* [n_chunks]  tokens in the chunk (<= chunk_size)        */
-    const int64_t *chunk_prefix_len;   /* [n_chunks]  tokens of the same sequence in earlier chunks */
+    const int64_t *chunk_prefix_len;   /* [n_chunks]  tokens of the same sequence in earlier chunks (of the tail's
+                                          sequence for a chunk that holds a merged tail)          */
     const int32_t *chunk_group;        /* [n_chunks]                                            */
     const int32_t *chunk_idx_in_group; /* [n_chunks]  0-based                                   */
     const int64_t *seg_seq_id;         /* [n_segments] index into seq_lens                      */
@@ -80,7 +99,7 @@ typedef struct {
                                           chunk_seg_ptr[c] + c                                   */
     const int64_t *group_chunk_ptr;    /* [n_groups+1]                                          */
     const int64_t *group_chunks;       /* [n_chunks]  chunk ids per group, ascending dependency (forward) order */
-    const int64_t *group_seq_id;       /* [n_groups]  the long sequence, or -1 for a packed chunk */
+    const int64_t *group_seq_id;       /* [n_groups]  the split sequence, or -1 for a packed chunk that depends on none */
 } cf_plan_view;
 int cf_plan_get(const cf_plan *plan, cf_plan_view *out);
 

@@ -5,7 +5,8 @@ paper leaves a choice open the reading is stated at the step that takes it.
 
 A chunk is a dict:
     tokens      number of tokens in the chunk (<= chunk_size)
-    prefix_len  tokens of the same long sequence that lie in earlier chunks (0 for packed chunks)
+    prefix_len  tokens of the same long sequence that lie in earlier chunks (0 for packed chunks
+                that hold no slice of a split sequence)
     group       id of its dependency group; idx_in_group its 0-based position there
     segments    list of (seq_id, seq_start, length): which tokens of which input sequence
 A group is a dict: seq_id (the long sequence, or -1 for a packed chunk) and chunks (ids, ascending
@@ -13,26 +14,41 @@ dependency order = forward order).
 """
 
 
-def _try_pack(order, lens, n_bins, cap):
+def _try_pack(order, n_bins, cap):
     """One bin-packing attempt (Algorithm 1, the 'try binpacking into BinCnt bins' step).
 
-    The paper names no heuristic.  Reading: sequences, longest first, each go to the bin with
-    the smallest load (ties: lowest bin number), which keeps the chunks about equally full as
-    section 1 asks; the attempt fails as soon as a sequence does not fit there.
+    order: items (seq_id, seq_start, length, is_tail), longest first.
+    The paper names no heuristic.  Reading: each item goes to the bin with the smallest load (ties:
+    lowest bin number), which keeps the chunks about equally full as section 1 asks; the attempt
+    fails as soon as an item does not fit there.  With merged tails (see build_chunks) a tail only
+    considers bins that hold no tail yet, and fails when there is none.
     """
     load = [0] * n_bins
+    tails = [0] * n_bins
     members = [[] for _ in range(n_bins)]
-    for i in order:
-        b = min(range(n_bins), key=lambda x: (load[x], x))
-        if load[b] + lens[i] > cap:          # limit is inclusive: a bin may be exactly full
+    for item in order:
+        length, is_tail = item[2], item[3]
+        allowed = [x for x in range(n_bins) if not (is_tail and tails[x])]
+        if not allowed:
             return None
-        load[b] += lens[i]
-        members[b].append(i)
+        b = min(allowed, key=lambda x: (load[x], x))
+        if load[b] + length > cap:           # limit is inclusive: a bin may be exactly full
+            return None
+        load[b] += length
+        tails[b] += is_tail
+        members[b].append(item)
     return members
 
 
-def build_chunks(seq_lens, chunk_size):
-    """Algorithm 1.  Returns (chunks, groups)."""
+def build_chunks(seq_lens, chunk_size, merge_tails=False):
+    """Algorithm 1.  Returns (chunks, groups).
+
+    merge_tails: a variant the algorithm leaves open (its listing appends every slice of a split
+    sequence as a chunk of its own).  The last slice of a split sequence, when shorter than
+    ChunkSize, becomes one more item of the bin-packing instead, so that it shares a chunk with
+    short sequences; a chunk takes at most one tail, and the chunk that holds it is the last chunk
+    of that sequence's dependency group.
+    """
     lens = [int(x) for x in seq_lens]
     cap = int(chunk_size)
     if cap < 1 or any(x < 1 for x in lens):
@@ -41,36 +57,48 @@ def build_chunks(seq_lens, chunk_size):
     # 'longer than ChunkSize' are split; a sequence of exactly ChunkSize tokens is one full
     # standalone chunk (the paper's example: a 2-Unit sequence with ChunkSize 2 Units).
     long_ids = [i for i, x in enumerate(lens) if x > cap]
-    short_ids = [i for i, x in enumerate(lens) if x <= cap]
+    items = [(i, 0, x, False) for i, x in enumerate(lens) if x <= cap]
 
     chunks, groups = [], []
+    tail_group = {}
     for i in long_ids:                       # input order
         gid = len(groups)
         groups.append({"seq_id": i, "chunks": []})
         start, m = 0, 0
         while start < lens[i]:
             n = min(cap, lens[i] - start)
+            if merge_tails and n < cap:
+                items.append((i, start, n, True))
+                tail_group[i] = (gid, m)
+                break
             groups[gid]["chunks"].append(len(chunks))
             chunks.append({"tokens": n, "prefix_len": start, "group": gid, "idx_in_group": m,
                            "segments": [(i, start, n)]})
             start += n
             m += 1
 
-    if short_ids:
-        order = sorted(short_ids, key=lambda i: (-lens[i], i))
+    if items:
+        order = sorted(items, key=lambda it: (-it[2], it[0]))
         bins = None
-        for n_bins in range(1, len(short_ids) + 1):     # first bin count that works wins
-            bins = _try_pack(order, lens, n_bins, cap)
+        for n_bins in range(1, len(items) + 1):         # first bin count that works wins
+            bins = _try_pack(order, n_bins, cap)
             if bins is not None:
                 break
         for members in bins:
             if not members:
                 continue
-            gid = len(groups)
-            groups.append({"seq_id": -1, "chunks": [len(chunks)]})
-            segs = [(i, 0, lens[i]) for i in sorted(members)]   # input order inside a chunk
-            chunks.append({"tokens": sum(s[2] for s in segs), "prefix_len": 0, "group": gid,
-                           "idx_in_group": 0, "segments": segs})
+            members = sorted(members)                    # input order inside a chunk
+            segs = [(i, start, n) for (i, start, n, _) in members]
+            tail = [it for it in members if it[3]]
+            if tail:
+                gid, m = tail_group[tail[0][0]]
+                groups[gid]["chunks"].append(len(chunks))
+                prefix = tail[0][1]
+            else:
+                gid, m, prefix = len(groups), 0, 0
+                groups.append({"seq_id": -1, "chunks": [len(chunks)]})
+            chunks.append({"tokens": sum(s[2] for s in segs), "prefix_len": prefix, "group": gid,
+                           "idx_in_group": m, "segments": segs})
     return chunks, groups
 
 
@@ -135,6 +163,7 @@ def schedule_stats(chunks, groups, K):
     assert not kept
     st["n_reforward"] = st["n_forward"] - len(chunks)
     for g in groups:
-        if g["seq_id"] >= 0:
-            st["state_tokens"] = max(st["state_tokens"], sum(tokens[c] for c in g["chunks"]))
+        if g["seq_id"] >= 0:     # the split sequence's own tokens (a chunk with a merged tail also holds others)
+            own = sum(n for c in g["chunks"] for (sid, _, n) in chunks[c]["segments"] if sid == g["seq_id"])
+            st["state_tokens"] = max(st["state_tokens"], own)
     return st

@@ -16,7 +16,9 @@ CF_BF16, CF_FP32 = 0, 1
 CF_FLAG_SCALAR_KERNELS = 1
 CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
-EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_plan_free", "cf_plan_get",
+CF_PLAN_MERGE_TAILS = 1
+
+EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_build_chunks_ex", "cf_plan_free", "cf_plan_get",
            "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_attn_fwd_batch", "cf_attn_bwd_batch",
            "cf_count_pairs", "cf_profile_next_call"]
 
@@ -80,6 +82,7 @@ def lib():
         L.cf_last_error.restype = C.c_char_p
         L.cf_version.restype = C.c_int
         L.cf_build_chunks.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(C.c_void_p)]
+        L.cf_build_chunks_ex.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_uint32, C.POINTER(C.c_void_p)]
         L.cf_plan_free.argtypes = [C.c_void_p]
         L.cf_plan_free.restype = None
         L.cf_plan_get.argtypes = [C.c_void_p, C.POINTER(PlanView)]
@@ -172,6 +175,13 @@ def cf_build_chunks(seq_lens, chunk_size):
     lens = np.ascontiguousarray(seq_lens, dtype=np.int64)
     h = C.c_void_p()
     _check(lib().cf_build_chunks(lens.ctypes.data_as(C.c_void_p), len(lens), int(chunk_size), C.byref(h)))
+    return Plan(h)
+
+
+def cf_build_chunks_ex(seq_lens, chunk_size, flags):
+    lens = np.ascontiguousarray(seq_lens, dtype=np.int64)
+    h = C.c_void_p()
+    _check(lib().cf_build_chunks_ex(lens.ctypes.data_as(C.c_void_p), len(lens), int(chunk_size), int(flags), C.byref(h)))
     return Plan(h)
 
 

@@ -61,78 +61,147 @@ struct cf_plan {
     }
 };
 
-// One packing attempt: sequences in `order` (longest first) each go to the least-loaded bin, ties
-// to the lowest bin index.  Fails as soon as a bin would exceed `cap`.
-static bool try_pack(const std::vector<int64_t> &order, const int64_t *lens, int64_t n_bins,
-                     int64_t cap, std::vector<std::vector<int64_t>> &bins)
+// One item of the packing: the whole short sequence `seq`, or (is_tail) the last, partial slice of a split one.
+struct PackItem {
+    int64_t seq, start;
+    int32_t len;
+    bool is_tail;
+};
+
+// One packing attempt: items in `order` (longest first) each go to the least-loaded bin, ties to the lowest bin
+// index; a tail only goes to a bin that holds no tail yet (a chunk then depends on at most one split sequence).
+// Fails as soon as an item does not fit its bin, or a tail finds no tail-free bin.
+static bool try_pack(const std::vector<PackItem> &order, int64_t n_bins, int64_t cap,
+                     std::vector<std::vector<int64_t>> &bins)
 {
-    using Item = std::pair<int64_t, int64_t>;  // (load, bin): the smallest pair is the target bin
-    std::priority_queue<Item, std::vector<Item>, std::greater<Item>> heap;
+    using Entry = std::pair<int64_t, int64_t>;  // (load, bin): the smallest pair is the target bin
+    std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
+    std::vector<int64_t> load((size_t)n_bins, 0);
+    std::vector<char> has_tail((size_t)n_bins, 0);
     for (int64_t b = 0; b < n_bins; ++b) heap.push({0, b});
     bins.assign((size_t)n_bins, {});
-    for (int64_t i : order) {
-        Item top = heap.top();
-        heap.pop();
-        if (top.first + lens[i] > cap) return false;
-        top.first += lens[i];
-        bins[(size_t)top.second].push_back(i);
-        heap.push(top);
+    for (size_t n = 0; n < order.size(); ++n) {
+        const PackItem &it = order[n];
+        int64_t b = -1;
+        if (!it.is_tail) {
+            while (heap.top().first != load[(size_t)heap.top().second]) heap.pop();   // entries a tail made stale
+            b = heap.top().second;
+            heap.pop();
+        } else {
+            for (int64_t x = 0; x < n_bins; ++x)
+                if (!has_tail[(size_t)x] && (b < 0 || load[(size_t)x] < load[(size_t)b])) b = x;
+            if (b < 0) return false;
+            has_tail[(size_t)b] = 1;
+        }
+        if (load[(size_t)b] + it.len > cap) return false;
+        load[(size_t)b] += it.len;
+        bins[(size_t)b].push_back((int64_t)n);
+        heap.push({load[(size_t)b], b});
     }
     return true;
 }
 
-extern "C" int cf_build_chunks(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size,
-                               cf_plan **out)
+extern "C" int cf_build_chunks_ex(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size, uint32_t flags,
+                                  cf_plan **out)
 {
     if (!out) return cf::fail(CF_EINVAL, "cf_build_chunks: out is NULL");
     if (n_seqs < 0) return cf::fail(CF_EINVAL, "cf_build_chunks: n_seqs = %lld < 0", (long long)n_seqs);
     if (n_seqs > 0 && !seq_lens) return cf::fail(CF_EINVAL, "cf_build_chunks: seq_lens is NULL");
     if (chunk_size < 1 || chunk_size > INT32_MAX)
         return cf::fail(CF_EINVAL, "cf_build_chunks: chunk_size %lld outside [1, 2^31)", (long long)chunk_size);
+    if (flags & ~(uint32_t)CF_PLAN_MERGE_TAILS)
+        return cf::fail(CF_EINVAL, "cf_build_chunks_ex: unknown flags 0x%x", flags);
     for (int64_t i = 0; i < n_seqs; ++i)
         if (seq_lens[i] < 1)
             return cf::fail(CF_EINVAL, "cf_build_chunks: seq_lens[%lld] = %lld < 1", (long long)i,
                             (long long)seq_lens[i]);
+    const bool merge_tails = flags & CF_PLAN_MERGE_TAILS;
     cf_plan *p = nullptr;
     try {
         p = new cf_plan();
         p->chunk_size = chunk_size;
         const int64_t C = chunk_size;
-        std::vector<int64_t> shorts;
-        int64_t short_tokens = 0;
+        std::vector<PackItem> items;     // what the packing places: short sequences and, if asked, tails
+        std::vector<int32_t> tail_group((size_t)n_seqs, -1), tail_idx((size_t)n_seqs, 0);
+        int64_t item_tokens = 0;
         for (int64_t i = 0; i < n_seqs; ++i) {
             p->total_tokens += seq_lens[i];
             if (seq_lens[i] <= C) {  // exactly chunk_size tokens: one full standalone chunk
-                shorts.push_back(i);
-                short_tokens += seq_lens[i];
+                items.push_back({i, 0, (int32_t)seq_lens[i], false});
+                item_tokens += seq_lens[i];
                 continue;
             }
             const int32_t group = (int32_t)p->group_seq_id.size();
             int32_t m = 0;
-            for (int64_t start = 0; start < seq_lens[i]; start += C, ++m)
-                p->add_chunk(group, m, start, {i}, {start}, {(int32_t)std::min(C, seq_lens[i] - start)});
+            for (int64_t start = 0; start < seq_lens[i]; start += C, ++m) {
+                const int32_t n = (int32_t)std::min(C, seq_lens[i] - start);
+                if (merge_tails && n < C) {          // the partial last slice joins the packing instead
+                    items.push_back({i, start, n, true});
+                    item_tokens += n;
+                    tail_group[(size_t)i] = group;
+                    tail_idx[(size_t)i] = m;
+                    break;
+                }
+                p->add_chunk(group, m, start, {i}, {start}, {n});
+            }
             p->group_seq_id.push_back(i);
             p->group_chunk_ptr.push_back((int64_t)p->group_chunks.size());
         }
-        if (!shorts.empty()) {
-            std::vector<int64_t> order = shorts;
+        if (!items.empty()) {
+            std::vector<PackItem> order = items;     // items are in sequence order: a stable sort keeps it among equals
             std::stable_sort(order.begin(), order.end(),
-                             [&](int64_t a, int64_t b) { return seq_lens[a] > seq_lens[b]; });
+                             [](const PackItem &a, const PackItem &b) { return a.len > b.len; });
             // Bin counts below ceil(tokens / C) cannot hold the tokens, so every attempt there fails:
             // starting at that count gives the same answer as starting at 1.
             std::vector<std::vector<int64_t>> bins;
-            int64_t n_bins = std::max<int64_t>(1, (short_tokens + C - 1) / C);
-            while (!try_pack(order, seq_lens, n_bins, C, bins)) ++n_bins;
+            int64_t n_bins = std::max<int64_t>(1, (item_tokens + C - 1) / C);
+            while (!try_pack(order, n_bins, C, bins)) ++n_bins;
+            // A chunk that holds a tail is the last chunk of that sequence's group; it is inserted into the
+            // group lists afterwards (group_chunks is laid out group by group).
+            std::vector<std::vector<int64_t>> extra(p->group_seq_id.size());
+            std::vector<int64_t> packed_chunks;
             for (auto &members : bins) {
                 if (members.empty()) continue;
-                std::sort(members.begin(), members.end());
-                std::vector<int64_t> starts(members.size(), 0);
+                std::sort(members.begin(), members.end(),
+                          [&](int64_t a, int64_t b) { return order[(size_t)a].seq < order[(size_t)b].seq; });
+                std::vector<int64_t> ids, starts;
                 std::vector<int32_t> lens;
-                for (int64_t i : members) lens.push_back((int32_t)seq_lens[i]);
-                p->add_chunk((int32_t)p->group_seq_id.size(), 0, 0, members, starts, lens);
-                p->group_seq_id.push_back(-1);
-                p->group_chunk_ptr.push_back((int64_t)p->group_chunks.size());
+                int64_t prefix = 0;
+                int32_t group = -1, idx = 0;
+                for (int64_t n : members) {
+                    const PackItem &it = order[(size_t)n];
+                    ids.push_back(it.seq);
+                    starts.push_back(it.start);
+                    lens.push_back(it.len);
+                    if (it.is_tail) {
+                        prefix = it.start;
+                        group = tail_group[(size_t)it.seq];
+                        idx = tail_idx[(size_t)it.seq];
+                    }
+                }
+                const int64_t chunk_id = (int64_t)p->chunk_tokens.size();
+                p->add_chunk(group, idx, prefix, ids, starts, lens);
+                p->group_chunks.pop_back();          // placed below, where its group's list is
+                if (group >= 0) extra[(size_t)group].push_back(chunk_id);
+                else packed_chunks.push_back(chunk_id);
             }
+            // rebuild the group lists: split sequences (slices, then the chunk with their tail), then one group per
+            // remaining packed chunk
+            std::vector<int64_t> chunks_of, ptr{0};
+            const size_t n_long = p->group_seq_id.size();
+            for (size_t g = 0; g < n_long; ++g) {
+                for (int64_t j = p->group_chunk_ptr[g]; j < p->group_chunk_ptr[g + 1]; ++j) chunks_of.push_back(p->group_chunks[(size_t)j]);
+                for (int64_t c : extra[g]) chunks_of.push_back(c);
+                ptr.push_back((int64_t)chunks_of.size());
+            }
+            for (int64_t c : packed_chunks) {
+                p->chunk_group[(size_t)c] = (int32_t)p->group_seq_id.size();
+                p->group_seq_id.push_back(-1);
+                chunks_of.push_back(c);
+                ptr.push_back((int64_t)chunks_of.size());
+            }
+            p->group_chunks = chunks_of;
+            p->group_chunk_ptr = ptr;
         }
     } catch (const std::bad_alloc &) {
         delete p;
@@ -140,6 +209,11 @@ extern "C" int cf_build_chunks(const int64_t *seq_lens, int64_t n_seqs, int64_t 
     }
     *out = p;
     return CF_OK;
+}
+
+extern "C" int cf_build_chunks(const int64_t *seq_lens, int64_t n_seqs, int64_t chunk_size, cf_plan **out)
+{
+    return cf_build_chunks_ex(seq_lens, n_seqs, chunk_size, 0, out);
 }
 
 extern "C" void cf_plan_free(cf_plan *plan) { delete plan; }
@@ -222,8 +296,12 @@ extern "C" int cf_schedule_stats(cf_plan *p, int32_t K, cf_sched_stats *out)
     const int64_t n_groups = (int64_t)p->group_seq_id.size();
     for (int64_t g = 0; g < n_groups; ++g) {
         if (p->group_seq_id[g] < 0) continue;          // packed chunk: no state
-        int64_t len = 0;
-        for (int64_t j = p->group_chunk_ptr[g]; j < p->group_chunk_ptr[g + 1]; ++j) len += p->chunk_tokens[p->group_chunks[j]];
+        int64_t len = 0;   // the split sequence's own tokens (a chunk with a merged tail also holds others)
+        for (int64_t j = p->group_chunk_ptr[g]; j < p->group_chunk_ptr[g + 1]; ++j) {
+            const int64_t c = p->group_chunks[j];
+            for (int64_t s = p->chunk_seg_ptr[c]; s < p->chunk_seg_ptr[c + 1]; ++s)
+                if (p->seg_seq_id[s] == p->group_seq_id[g]) len += p->seg_len[s];
+        }
         if (len > st.state_tokens) st.state_tokens = len;
     }
     *out = st;

@@ -62,6 +62,8 @@ class ChunkAttention:
         # All fp32 dK/dV buffers (per long sequence, per packed chunk) are slices of ONE allocation, so that zeroing
         # the gradients of a step is one fill.
         row = self.Hkv * self.D
+        # (every key row of the batch appears in exactly one buffer: a split sequence's rows in its state, a
+        # short sequence's in its chunk)
         self.grad_arena = torch.zeros(2 * int(p.total_tokens) * row, dtype=torch.float32, device=dev)
         self._grad_used = 0
 
@@ -71,12 +73,40 @@ class ChunkAttention:
             dk = self.grad_arena[a:a + n_rows * row].view(n_rows, self.Hkv, self.D)
             dv = self.grad_arena[a + n_rows * row:a + 2 * n_rows * row].view(n_rows, self.Hkv, self.D)
             return dk, dv
+        def group_state(g):
+            """Key/value state and its fp32 gradients of the split sequence of group g, created at the group's
+            first chunk.  When the group's last chunk also holds other sequences (a merged tail), the state is a
+            slice of that chunk's key/value buffer, so that the chunk's keys are one contiguous array."""
+            if g in self.state:
+                return self.state[g]
+            sid = int(p.group_seq_id[g])
+            L = seq_len[sid]
+            vals = get(sid, L)
+            last_segs = p.chunk_segments(int(p.group(g)[-1]))
+            if len(last_segs) == 1:
+                gdk, gdv = grad_pair(L)
+                st = {"k": up(vals["k"]), "v": up(vals["v"]), "dk": gdk, "dv": gdv}
+            else:
+                cu_k = np.concatenate([[0], np.cumsum([start + n for (_, start, n) in last_segs])]).astype(np.int32)
+                rows = int(cu_k[-1])
+                kbuf = torch.empty((rows, self.Hkv, self.D), dtype=dt, device=dev)
+                vbuf = torch.empty_like(kbuf)
+                gdk, gdv = grad_pair(rows)
+                a = int(cu_k[[s[0] for s in last_segs].index(sid)])
+                kbuf[a:a + L].copy_(up(vals["k"]))
+                vbuf[a:a + L].copy_(up(vals["v"]))
+                st = {"k": kbuf[a:a + L], "v": vbuf[a:a + L], "dk": gdk[a:a + L], "dv": gdv[a:a + L],
+                      "merged": {"k": kbuf, "v": vbuf, "dk": gdk, "dv": gdv, "cu_k": cu_k}}
+            self.state[g] = st
+            return st
+
         for c in range(p.n_chunks):
             segs = p.chunk_segments(c)
             T, P = int(p.chunk_tokens[c]), int(p.chunk_prefix_len[c])
             g = int(p.chunk_group[c])
             dependent = int(p.group_seq_id[g]) >= 0
-            ch = {"T": T, "P": P, "dependent": dependent, "segs": segs, "group": g}
+            merged = dependent and len(segs) > 1
+            ch = {"T": T, "P": P, "dependent": dependent, "merged": merged, "segs": segs, "group": g}
             ch["q"] = torch.empty((T, self.Hq, self.D), dtype=dt, device=dev)
             ch["d_o"] = torch.empty_like(ch["q"])
             ch["o"] = torch.empty_like(ch["q"])
@@ -85,19 +115,30 @@ class ChunkAttention:
             cu = p.chunk_cu_seqlens(c)
             ch["cu_q_host"] = cu.copy()
             ch["cu_q"] = torch.from_numpy(cu.copy()).to(dev)
-            if dependent:
+            if dependent and not merged:
                 sid, start, n = segs[0]
                 L = seq_len[sid]
+                st = group_state(g)
                 vals = get(sid, L)
-                if g not in self.state:
-                    gdk, gdv = grad_pair(L)
-                    self.state[g] = {"k": up(vals["k"]), "v": up(vals["v"]), "dk": gdk, "dv": gdv}
-                st = self.state[g]
                 ch["k"], ch["v"] = st["k"][:P + T], st["v"][:P + T]
                 ch["dk"], ch["dv"] = st["dk"][:P + T], st["dv"][:P + T]
                 ch["q"].copy_(up(vals["q"][start:start + n]))
                 ch["d_o"].copy_(up(vals["d_o"][start:start + n]))
                 ch["cu_k_host"] = np.array([0, P + T], dtype=np.int32)
+            elif merged:
+                # short sequences plus the last slice of the group's split sequence, whose keys are its whole state
+                M = group_state(g)["merged"]
+                ch["k"], ch["v"], ch["dk"], ch["dv"] = M["k"], M["v"], M["dk"], M["dv"]
+                ch["cu_k_host"] = M["cu_k"].copy()
+                for i, (sid, start, n) in enumerate(segs):
+                    vals = get(sid, seq_len[sid])
+                    a, b = int(cu[i]), int(cu[i + 1])
+                    ch["q"][a:b].copy_(up(vals["q"][start:start + n]))
+                    ch["d_o"][a:b].copy_(up(vals["d_o"][start:start + n]))
+                    if start == 0:           # (the state rows were filled when the group was first met)
+                        ka = int(M["cu_k"][i])
+                        ch["k"][ka:ka + n].copy_(up(vals["k"]))
+                        ch["v"][ka:ka + n].copy_(up(vals["v"]))
             else:
                 ch["k"] = torch.empty((T, self.Hkv, self.D), dtype=dt, device=dev)
                 ch["v"] = torch.empty_like(ch["k"])
@@ -194,17 +235,18 @@ class ChunkAttention:
         torch.cuda.synchronize()
         out = {}
         f64 = lambda t: t.detach().to(torch.float64).cpu().numpy()
+        split = {int(self.plan.group_seq_id[g]): g for g in self.state}     # split sequence -> its group
         for ch in self.chunks:
             o, lse, dq = f64(ch["o"]), f64(ch["lse"]), f64(ch["d_q"])
             dk = dv = None
-            if not ch["dependent"]:
+            if not ch["dependent"] or ch["merged"]:
                 dk, dv = f64(ch["dk"]), f64(ch["dv"])
-            cu = ch["cu_q_host"]
+            cu, cu_k = ch["cu_q_host"], ch["cu_k_host"]
             for i, (sid, start, n) in enumerate(ch["segs"]):
                 a, b = int(cu[i]), int(cu[i + 1])
                 r = out.setdefault(sid, {})
-                if ch["dependent"]:
-                    st = self.state[ch["group"]]
+                if sid in split:
+                    st = self.state[split[sid]]
                     L = st["k"].shape[0]
                     if "o" not in r:
                         r.update(o=np.zeros((L, self.Hq, self.D)), lse=np.zeros((self.Hq, L)),
@@ -212,5 +254,6 @@ class ChunkAttention:
                     r["o"][start:start + n], r["dq"][start:start + n] = o[a:b], dq[a:b]
                     r["lse"][:, start:start + n] = lse[:, a:b]
                 else:
-                    r.update(o=o[a:b], lse=lse[:, a:b], dq=dq[a:b], dk=dk[a:b], dv=dv[a:b])
+                    ka = int(cu_k[i])
+                    r.update(o=o[a:b], lse=lse[:, a:b], dq=dq[a:b], dk=dk[ka:ka + n], dv=dv[ka:ka + n])
         return out

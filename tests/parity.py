@@ -41,9 +41,10 @@ def check(got, ref, dtype, what=""):
     return errs
 
 
-def run_gpu(lens, C, Hq, Hkv, D, dtype, seed, flags=0, K=None, scale=None, fused_launch=False, n_streams=1):
+def run_gpu(lens, C, Hq, Hkv, D, dtype, seed, flags=0, K=None, scale=None, fused_launch=False, n_streams=1,
+            merge_tails=False):
     """Chunk-plan the lengths with the library, run forward+backward on the GPU, return per-sequence results."""
-    plan = B.cf_build_chunks(lens, C)
+    plan = B.cf_build_chunks_ex(lens, C, B.CF_PLAN_MERGE_TAILS) if merge_tails else B.cf_build_chunks(lens, C)
     vals = lambda sid, L: inputs.seq_values(seed, sid, lens[sid], Hq, Hkv, D, dtype)
     eng = ChunkAttention(plan, Hq, Hkv, D, dtype, scale=scale, flags=flags, fused_launch=fused_launch,
                          n_streams=n_streams).load(vals)

@@ -77,6 +77,20 @@ def test_many_tiny_documents_in_one_chunk(flags):
     P.check(got, ref, "bf16", "300 tiny documents")
 
 
+@pytest.mark.parametrize("dtype,D,flags,K,fused", [("bf16", 128, 0, None, False), ("bf16", 128, 0, 1, False),
+                                                    ("bf16", 128, 0, None, True), ("bf16", 128, SCALAR, None, False),
+                                                    ("fp32", 64, 0, 2, False)])
+def test_merged_tails_plan(dtype, D, flags, K, fused):
+    """Algorithm 1's variant that packs the last slice of a split sequence with short sequences: chunks whose
+    segments mix a slice that reads its sequence's key/value state with whole short sequences."""
+    lens = [700, 40, 300, 33, 1000, 129, 64, 5, 450, 17, 260, 90]
+    C = 256
+    got, eng = P.run_gpu(lens, C, 4, 2, D, dtype, seed=9, flags=flags, K=K, fused_launch=fused, merge_tails=True)
+    assert sum(ch["merged"] for ch in eng.chunks) >= 2           # 700 -> tail 188, 1000 -> tail 232, 450 -> tail 194
+    ref = P.run_oracle(lens, 4, 2, D, dtype, seed=9)
+    P.check(got, ref, dtype, f"merged tails {dtype} D={D} flags={flags} K={K} fused={fused}")
+
+
 def test_recompute_schedule_gives_same_result():
     """Algorithm 2 with K=1: the first N-1 chunks run forward twice; results must not change."""
     lens = [900, 40, 300]

@@ -195,6 +195,24 @@ def test_chunked_equals_unsplit(C):
                                        err_msg=f"seq {sid} {name} C={C}")
 
 
+@pytest.mark.parametrize("C", [16, 25, 40])
+def test_chunked_with_merged_tails_equals_unsplit(C):
+    """The same equivalence when the last slice of a split sequence shares a chunk with short sequences
+    (a chunk whose segments mix 'keys longer than queries' with plain ones)."""
+    rng = np.random.default_rng(8)
+    lens = [5, 70, 16, 1, 33, 9, 12, 51, 3]
+    Hq, Hkv, D, scale = 4, 2, 8, 0.35
+    seqs = make_seqs(rng, lens, Hq, Hkv, D)
+    chunks, groups = CK.build_chunks(lens, C, merge_tails=True)
+    assert any(len(c["segments"]) > 1 and c["prefix_len"] > 0 for c in chunks)      # the case is exercised
+    got = run_plan(chunks, groups, seqs, scale)
+    ref = run_unsplit(seqs, scale)
+    for sid in seqs:
+        for name in ("o", "lse", "dq", "dk", "dv"):
+            np.testing.assert_allclose(got[sid][name], ref[sid][name], atol=1e-12, rtol=0,
+                                       err_msg=f"seq {sid} {name} C={C}")
+
+
 def test_packed_chunk_equals_sequences_run_alone():
     rng = np.random.default_rng(7)
     lens = [4, 9, 1, 6]

@@ -179,3 +179,69 @@ def test_schedule_stats_kept_memory_follows_chunk_size():
             assert st["state_tokens"] == 40000
         peaks.append(CK.schedule_stats(chunks, groups, 1)["peak_kept_tokens"])
     assert peaks == [2048, 4096, 8192]
+
+
+# ---------------------------------------------------------------- merged tails (variant of Algorithm 1)
+
+def check_valid_merged(lens, C, chunks, groups):
+    """What must hold for any reading of 'the last slice joins the bin-packing': every token once, chunks within
+    ChunkSize, full slices first in their group, at most one tail per chunk and that chunk last in the tail's group."""
+    seen = {i: np.zeros(L, int) for i, L in enumerate(lens)}
+    for cid, c in enumerate(chunks):
+        assert 1 <= c["tokens"] <= C and c["tokens"] == sum(s[2] for s in c["segments"])
+        for (sid, st, n) in c["segments"]:
+            seen[sid][st:st + n] += 1
+        g = groups[c["group"]]
+        assert g["chunks"][c["idx_in_group"]] == cid
+        assert [s[0] for s in c["segments"]] == sorted(s[0] for s in c["segments"])
+        slices = [(sid, st, n) for (sid, st, n) in c["segments"] if lens[sid] > C]
+        assert len(slices) <= 1
+        if g["seq_id"] >= 0:
+            (sid, st, n), = slices
+            assert sid == g["seq_id"] and st == c["prefix_len"] == c["idx_in_group"] * C
+            if n == C:
+                assert len(c["segments"]) == 1                       # a full slice is alone
+            else:
+                assert c["idx_in_group"] == len(g["chunks"]) - 1 and n == lens[sid] - st
+        else:
+            assert not slices and c["prefix_len"] == 0 and len(g["chunks"]) == 1
+        assert all(st == 0 and n == lens[sid] for (sid, st, n) in c["segments"] if lens[sid] <= C)
+    assert all((v == 1).all() for v in seen.values())
+
+
+def test_merged_tails_worked_examples():
+    # 5 tokens, ChunkSize 2: two full slices and a 1-token tail (prefix 4).  Items of length 1: the tail (sequence 0),
+    # sequences 1 and 2; 3 tokens need 2 bins; tail -> bin 0, sequence 1 -> bin 1, sequence 2 -> bin 0 (tie: lowest).
+    chunks, groups = CK.build_chunks([5, 1, 1], 2, merge_tails=True)
+    assert [c["segments"] for c in chunks] == [[(0, 0, 2)], [(0, 2, 2)], [(0, 4, 1), (2, 0, 1)], [(1, 0, 1)]]
+    assert [c["prefix_len"] for c in chunks] == [0, 2, 4, 0]
+    assert groups == [{"seq_id": 0, "chunks": [0, 1, 2]}, {"seq_id": -1, "chunks": [3]}]
+    # without the option the tail is a chunk of its own and the two short sequences share one
+    plain, _ = CK.build_chunks([5, 1, 1], 2)
+    assert [c["segments"] for c in plain] == [[(0, 0, 2)], [(0, 2, 2)], [(0, 4, 1)], [(1, 0, 1), (2, 0, 1)]]
+    # two tails never share a chunk, even when they would fit: 2 bins although 2 tokens fit one
+    chunks, groups = CK.build_chunks([5, 5], 4, merge_tails=True)
+    assert [c["segments"] for c in chunks] == [[(0, 0, 4)], [(1, 0, 4)], [(0, 4, 1)], [(1, 4, 1)]]
+    assert [g["chunks"] for g in groups] == [[0, 2], [1, 3]]
+    # a sequence that is a whole number of chunks has no tail; nothing changes
+    assert CK.build_chunks([1, 1, 2, 4], 2, merge_tails=True) == CK.build_chunks([1, 1, 2, 4], 2)
+
+
+def test_merged_tails_random_lists_are_valid_and_save_chunks():
+    rng = np.random.default_rng(5)
+    fewer = 0
+    for trial in range(400):
+        n = int(rng.integers(0, 10))
+        C = int(rng.integers(1, 40))
+        lens = [int(x) for x in rng.integers(1, 4 * C + 2, size=n)]
+        chunks, groups = CK.build_chunks(lens, C, merge_tails=True)
+        check_valid_merged(lens, C, chunks, groups)
+        plain, _ = CK.build_chunks(lens, C)
+        assert len(chunks) >= -(-sum(lens) // C)            # cannot beat the token bound
+        fewer += len(chunks) < len(plain)
+        # schedules stay well-formed: every chunk forward and backward, groups contiguous
+        ops = CK.build_schedule(groups, 2)
+        assert sorted(c for op, c in ops if op == CK.BWD) == list(range(len(chunks)))
+        st = CK.schedule_stats(chunks, groups, 2)
+        assert st["state_tokens"] == max([x for x in lens if x > C], default=0)
+    assert fewer > 50                                       # the point of the variant

@@ -13,9 +13,9 @@ from paper_2503_02356_amd import inputs
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def assert_same_plan(lens, C):
-    chunks, groups = CK.build_chunks(lens, C)
-    p = B.cf_build_chunks(lens, C)
+def assert_same_plan(lens, C, merge_tails=False):
+    chunks, groups = CK.build_chunks(lens, C, merge_tails=merge_tails)
+    p = B.cf_build_chunks_ex(lens, C, B.CF_PLAN_MERGE_TAILS) if merge_tails else B.cf_build_chunks(lens, C)
     assert p.n_chunks == len(chunks) and p.n_groups == len(groups)
     assert p.total_tokens == int(np.sum(lens)) and p.chunk_size == C
     assert p.n_segments == sum(len(c["segments"]) for c in chunks)
@@ -29,6 +29,7 @@ def assert_same_plan(lens, C):
         assert p.group(g) == gr["chunks"] and int(p.group_seq_id[g]) == gr["seq_id"]
     for K in (1, 2, 5):
         assert p.schedule(K) == CK.build_schedule(groups, K)
+        assert p.schedule_stats(K) == CK.schedule_stats(chunks, groups, K)
     p.close()
     return len(chunks)
 
@@ -61,6 +62,25 @@ def test_random_lists_bit_exact():
         else:
             lens = rng.choice([1, C, C + 1, max(1, C // 2), 2 * C], size=n)     # boundary lengths, many ties
         assert_same_plan([int(x) for x in lens], C)
+
+
+def test_merged_tails_bit_exact():
+    assert assert_same_plan([5, 1, 1], 2, merge_tails=True) == 4
+    assert assert_same_plan([5, 5], 4, merge_tails=True) == 4
+    rng = np.random.default_rng(12)
+    for trial in range(600):
+        n = int(rng.integers(0, 40))
+        C = int(rng.integers(1, 200))
+        if trial % 2:
+            lens = rng.integers(1, 4 * C + 2, size=n)
+        else:
+            lens = rng.choice([1, C, C + 1, max(1, C // 2), 2 * C, 2 * C + 1, 3 * C - 1], size=n)
+        assert_same_plan([int(x) for x in lens], C, merge_tails=True)
+    # flags = 0 is cf_build_chunks; unknown bits are refused
+    a, b = B.cf_build_chunks_ex([9, 3, 3, 10, 1], 4, 0), B.cf_build_chunks([9, 3, 3, 10, 1], 4)
+    assert [a.chunk_segments(c) for c in range(a.n_chunks)] == [b.chunk_segments(c) for c in range(b.n_chunks)]
+    with pytest.raises(B.CfError):
+        B.cf_build_chunks_ex([3], 2, 2)
 
 
 @pytest.mark.parametrize("cfg,sd", [("tiny_fp32", 1), ("packed_8k", 1), ("long32k_mixed", 1),
