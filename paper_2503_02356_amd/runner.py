@@ -26,7 +26,7 @@ def schedule_memory(plan, K, n_q_heads, n_kv_heads, head_dim, elem_bytes=2):
 
 class ChunkAttention:
     def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0,
-                 n_streams=1, fused_launch=False):
+                 n_streams=1, fused_launch=False, only_groups=None):
         """n_streams > 1: dependency groups are dealt over that many HIP streams (default priority), so that
         the last, partly filled wave of workgroups of one chunk's kernel overlaps with the next group's
         kernels.  The chunks of one group stay on one stream, in the order of section 4.2."""
@@ -38,6 +38,9 @@ class ChunkAttention:
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(head_dim))
         self.dev, self.flags = torch.device(device), flags
+        # only_groups: place and run just these dependency groups of the plan (a batch too large for one GPU's
+        # memory is then run group by group, or sampled); the other chunks' entries stay None.
+        self.only_groups = None if only_groups is None else set(int(g) for g in only_groups)
         self.chunks = []          # per chunk: dict of device tensors and params
         self.state = {}           # group id -> dict(k, v, dk, dv) for long sequences
 
@@ -64,7 +67,9 @@ class ChunkAttention:
         row = self.Hkv * self.D
         # (every key row of the batch appears in exactly one buffer: a split sequence's rows in its state, a
         # short sequence's in its chunk)
-        self.grad_arena = torch.zeros(2 * int(p.total_tokens) * row, dtype=torch.float32, device=dev)
+        placed = lambda c: self.only_groups is None or int(p.chunk_group[c]) in self.only_groups
+        arena_rows = sum(int(p.chunk_tokens[c]) for c in range(p.n_chunks) if placed(c))
+        self.grad_arena = torch.zeros(2 * arena_rows * row, dtype=torch.float32, device=dev)
         self._grad_used = 0
 
         def grad_pair(n_rows):
@@ -104,6 +109,9 @@ class ChunkAttention:
             segs = p.chunk_segments(c)
             T, P = int(p.chunk_tokens[c]), int(p.chunk_prefix_len[c])
             g = int(p.chunk_group[c])
+            if not placed(c):
+                self.chunks.append(None)
+                continue
             dependent = int(p.group_seq_id[g]) >= 0
             merged = dependent and len(segs) > 1
             ch = {"T": T, "P": P, "dependent": dependent, "merged": merged, "segs": segs, "group": g}
@@ -162,11 +170,12 @@ class ChunkAttention:
         self.streams = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
         # groups go, in plan order, to the stream with the least work so far (work = unmasked pairs)
         load, lane_of = [0] * self.n_streams, {}
-        for ch in self.chunks:
+        placed_chunks = [ch for ch in self.chunks if ch is not None]
+        for ch in placed_chunks:
             if ch["group"] not in lane_of:
                 lane_of[ch["group"]] = load.index(min(load))
             load[lane_of[ch["group"]]] += ch["pairs"]
-        for ch in self.chunks:
+        for ch in placed_chunks:
             ch["lane"] = lane_of[ch["group"]]
             if self.fused_launch:       # the chunks of a fused call are in flight together: a workspace each
                 need = B.cf_attn_bwd_workspace_bytes(ch["fwd"])
@@ -176,18 +185,21 @@ class ChunkAttention:
         if self.fused_launch:
             self.fwd_batch = B.params_array([self.chunks[c]["fwd"] for c in self.forward_order()])
             self.bwd_batch = B.params_array([self.chunks[c]["bwd"] for c in self.backward_order()])
-        self.total_pairs = sum(ch["pairs"] for ch in self.chunks)
+        self.total_pairs = sum(ch["pairs"] for ch in placed_chunks)
         return self
 
     # ------------------------------------------------------------------ launches
     def zero_grads(self):
         self.grad_arena.zero_()
 
+    def groups(self):
+        return [g for g in range(self.plan.n_groups) if self.only_groups is None or g in self.only_groups]
+
     def forward_order(self):
-        return [c for g in range(self.plan.n_groups) for c in self.plan.group(g)]
+        return [c for g in self.groups() for c in self.plan.group(g)]
 
     def backward_order(self):
-        return [c for g in range(self.plan.n_groups) for c in reversed(self.plan.group(g))]
+        return [c for g in self.groups() for c in reversed(self.plan.group(g))]
 
     def _launch(self, ops):
         """ops: iterable of (is_backward, chunk id) in issue order.  One stream: plain launches on the current
@@ -227,7 +239,7 @@ class ChunkAttention:
     def run_schedule(self, K):
         """Algorithm 2 with K kept chunks: chunks marked FWD_DISCARD run forward (their K/V state is
         what later chunks need) and run forward again right before their backward."""
-        self._launch((op == B.CF_OP_BWD, c) for op, c in self.plan.schedule(K))
+        self._launch((op == B.CF_OP_BWD, c) for op, c in self.plan.schedule(K) if self.chunks[c] is not None)
 
     # ------------------------------------------------------------------ results
     def results(self):
@@ -237,6 +249,8 @@ class ChunkAttention:
         f64 = lambda t: t.detach().to(torch.float64).cpu().numpy()
         split = {int(self.plan.group_seq_id[g]): g for g in self.state}     # split sequence -> its group
         for ch in self.chunks:
+            if ch is None:
+                continue
             o, lse, dq = f64(ch["o"]), f64(ch["lse"]), f64(ch["d_q"])
             dk = dv = None
             if not ch["dependent"] or ch["merged"]:

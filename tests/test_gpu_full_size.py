@@ -1,4 +1,4 @@
-"""GPU parity at the FULL sizes of configs 2, 3 and 5, in the launch configuration bench.py times (one
+"""GPU parity at the FULL sizes of configs 2, 3, 4 and 5, in the launch configuration bench.py times (one
 cf_attn_fwd / cf_attn_bwd call per chunk through the plan runner).  The fp64 oracle cannot redo these
 sizes whole, so it recomputes sampled outputs one by one:
   - whole short sequences (all five tensors),
@@ -32,7 +32,8 @@ def device_values(cfg, seed, lens):
     return lambda sid: inputs.seq_values_device(seed, sid, lens[sid], HQ, HKV, D, "bf16", "cuda:0")
 
 
-def run_full(cfg, seed, on_device=False):
+def run_full(cfg, seed, on_device=False, pick_groups=None):
+    """pick_groups(plan, lens) -> group ids to place and run (None: the whole plan)."""
     HQ, HKV = inputs.CONFIGS[cfg]["Hq"], inputs.CONFIGS[cfg]["Hkv"]
 
     def count(lens, C):
@@ -44,7 +45,8 @@ def run_full(cfg, seed, on_device=False):
     lens = [int(x) for x in lens]
     plan = B.cf_build_chunks(lens, C)
     values = (device_values if on_device else host_values)(cfg, seed, lens)
-    eng = ChunkAttention(plan, HQ, HKV, D, "bf16").load(lambda sid, L: values(sid))
+    only = pick_groups(plan, lens) if pick_groups else None
+    eng = ChunkAttention(plan, HQ, HKV, D, "bf16", only_groups=only).load(lambda sid, L: values(sid))
     eng.zero_grads()
     eng.run_forward()
     eng.run_backward()
@@ -62,11 +64,12 @@ def check_short_sequences(lens, plan, eng, values, picks):
     HQ, HKV = eng.Hq, eng.Hkv
     where = {}
     for c, ch in enumerate(eng.chunks):
-        if not ch["dependent"]:
+        if ch is not None and not ch["dependent"]:
             for i, (sid, start, n) in enumerate(ch["segs"]):
                 where[sid] = (c, int(ch["cu_q_host"][i]), n)
     for sid in picks:
         c, a, n = where[sid]
+        print(f"oracle: sequence {sid}, {n} tokens ...", flush=True)
         ch = eng.chunks[c]
         v = {k: host(x) for k, x in values(sid).items()}
         o, lse = OA.seq_attn_fwd(v["q"], v["k"], v["v"], SCALE)
@@ -85,11 +88,11 @@ def test_config2_full_size_sampled_sequences():
     check_short_sequences(lens, plan, eng, values, picks)
 
 
-def check_long_sequence(lens, C, eng, values, rows, W):
-    """Sampled query rows (O, LSE, dQ) and the dK/dV of the last W keys of sequence 0, the long one."""
+def check_long_sequence(lens, C, eng, values, rows, W, sid=0):
+    """Sampled query rows (O, LSE, dQ) and the dK/dV of the last W keys of the split sequence sid."""
     HQ, HKV = eng.Hq, eng.Hkv
-    L = lens[0]
-    dev = values(0)
+    L = lens[sid]
+    dev = values(sid)
     # the oracle needs every key and value, but only the sampled rows of q and d_o
     v = {"k": host(dev["k"]), "v": host(dev["v"])}
     take = sorted(set(rows) | set(range(L - W, L)))
@@ -97,12 +100,13 @@ def check_long_sequence(lens, C, eng, values, rows, W):
     idx = take if not torch.is_tensor(dev["q"]) else torch.tensor(take, device=dev["q"].device)
     q_s, do_s = host(dev["q"][idx]), host(dev["d_o"][idx])
     del dev
-    g = eng.chunks[0]["group"]
+    g = [x for x in range(eng.plan.n_groups) if int(eng.plan.group_seq_id[x]) == sid][0]
+    group_chunks = eng.plan.group(g)
     got = {"o": [], "lse": [], "dq": []}
     ref = {"o": [], "lse": [], "dq": []}
     for r in rows:
         c, i = r // C, r % C
-        ch = eng.chunks[c]
+        ch = eng.chunks[group_chunks[c]]
         assert ch["dependent"] and ch["P"] == c * C
         n = at[r]
         o, lse = OA.chunk_attn_fwd(q_s[n:n + 1], v["k"][:r + 1], v["v"][:r + 1], [0, 1], [0, r + 1], SCALE)
@@ -149,3 +153,35 @@ def test_config5_full_size_sampled_rows_and_tail_keys():
     check_long_sequence(lens, C, eng, values, [0, 32767, 32768, 131072 + 63, 229376, 229376 + 12345, L - 1], 32)
     order = np.argsort(lens[1:]) + 1
     check_short_sequences(lens, plan, eng, values, [int(order[1]), int(order[len(order) // 2])])
+
+
+def test_config4_full_size_sampled_groups():
+    """The 20000-sequence long-tail batch (32 / 8 heads, chunk 16384) is planned whole; its tensors do not fit one
+    GPU at once, so the groups are run a few at a time as a training loop would: here the longest split sequence,
+    the shortest split sequence and two packed chunks (a middle one and the last), each checked against the oracle."""
+    cfg = "longtail_16k"
+    picked = {}
+
+    def pick(plan, lens):
+        split = sorted((lens[int(plan.group_seq_id[g])], g) for g in range(plan.n_groups) if int(plan.group_seq_id[g]) >= 0)
+        packed = [g for g in range(plan.n_groups) if int(plan.group_seq_id[g]) < 0]
+        mid = packed[len(packed) // 2]      # (the first packed chunks hold one ChunkSize-long sequence each)
+        picked.update(longest=split[-1][1], shortest=split[0][1], packed=[mid, packed[-1]])
+        return [split[-1][1], split[0][1], mid, packed[-1]]
+    lens, C, plan, eng, values = run_full(cfg, 0, on_device=True, pick_groups=pick)
+    assert len(lens) == 20000 and C == 16384 and plan.n_chunks > 900
+    for which, W in (("longest", 24), ("shortest", 64)):
+        sid = int(plan.group_seq_id[picked[which]])
+        L = lens[sid]
+        n_slices = -(-L // C)
+        assert len(plan.group(picked[which])) == n_slices
+        rows = sorted({0, C - 1, C, (n_slices - 1) * C, max(0, (n_slices - 1) * C - 1), L - 1, L // 2})
+        print(f"{which} split sequence {sid}: {L} tokens, {n_slices} slices", flush=True)
+        check_long_sequence(lens, C, eng, values, rows, min(W, L - (n_slices - 1) * C), sid=sid)
+    # whole short sequences of the two packed chunks (the oracle redoes each alone: keep them under 2000 tokens)
+    shorts = []
+    for g in picked["packed"]:
+        segs = [x for x in eng.chunks[plan.group(g)[0]]["segs"] if x[2] <= 2000]
+        by_len = sorted(segs, key=lambda x: x[2])
+        shorts += [by_len[0][0], by_len[len(by_len) // 2][0], by_len[-1][0]]
+    check_short_sequences(lens, plan, eng, values, shorts)
