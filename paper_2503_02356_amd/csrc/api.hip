@@ -62,7 +62,7 @@ int64_t delta_bytes(const cf_attn_fwd_params &p) { return round_up((int64_t)p.n_
 // counters (256 bytes) + two arrays of 16-byte items
 int64_t worklist_bytes(const cf_attn_fwd_params &p)
 {
-    return mfma_shape(p) ? 256 + 2 * cf::dkv_worklist_capacity(p) * 16 : 0;
+    return mfma_shape(p) ? 256 + cf::dkv_worklist_capacity(p) * 16 : 0;
 }
 
 int hip_fail(const char *who, hipError_t e)

@@ -56,46 +56,64 @@ static_assert(DKV_STAGE_BYTES >= 4 * 2 * EXCH_SLOT_BYTES, "exchange area too sma
 // One item = (segment, key tile, first head of the group's share, number of heads): the workgroups of one
 // key/value head.  A key tile seen by few query tiles keeps all G heads of the group in ONE item (one
 // prologue, one epilogue, one set of atomic updates instead of G); a tile seen by many query tiles is split
-// over up to G items so that no workgroup runs much longer than kSplitTarget tile iterations.  Items that come
-// out of a split go to the first array (they are the long ones and start first), the others to the second.
-// Workspace layout (ints): [0] = n_first, [1] = n_second, [64 ...] = first array, then second array; an item
+// over up to G items so that no workgroup runs much longer than kSplitTarget tile iterations.
+// The list is ordered by DESCENDING duration (heads x query tiles; a counting sort): workgroups start in list
+// order, and starting the longest first is what keeps the last compute units from running one long item alone
+// (a packed 8K chunk has ~500 items of 7 to 130 iterations for 256 compute units).
+// Workspace layout (ints): [0] = number of items, [1] = 0 (a second list, unused), [64 ...] = the items; an item
 // is int4 {segment, kt0, g0, n_heads}.
 constexpr int kSplitTarget = 48;
+constexpr int kDurationBuckets = 256;
 
 // Runs in ONE workgroup of any size: as a kernel of its own (whole-plan launches) or as the last workgroup of the dQ
 // launch, which the dK/dV kernel follows anyway (no launch of its own on the per-chunk path).
 __device__ __forceinline__ void build_dkv_worklist(const cf_attn_fwd_params &p, int *wl, int capacity)
 {
-    __shared__ int n_first, n_second;
-    if (threadIdx.x == 0) n_first = n_second = 0;
+    __shared__ int bucket[kDurationBuckets];        // items per duration, then the next free slot of each duration
+    __shared__ int n_items;
+    for (int i = threadIdx.x; i < kDurationBuckets; i += (int)blockDim.x) bucket[i] = 0;
     __syncthreads();
     const int G = p.n_q_heads / p.n_kv_heads;
-    i32x4 *first = (i32x4 *)(wl + 64), *second = first + capacity;
-    // Segments one after the other (their bounds are uniform loads), the key tiles of a segment in parallel.  The
-    // order inside an array follows the order in which the atomic counters are served: roughly ascending key
-    // tiles, i.e. the tiles seen by the most queries first.
-    for (int seg = 0; seg < p.n_segments; ++seg) {
-        const int lq = p.cu_seqlens_q[seg + 1] - p.cu_seqlens_q[seg];
-        const int lk = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
-        const int off = lk - lq;
-        const int n_head_qt = off < 128 ? min((lq + 63) / 64, (128 - off + 63) / 64) : 0;
-        for (int kt0 = threadIdx.x * 128; kt0 < lk; kt0 += (int)blockDim.x * 128) {
-            const int qt_first = kt0 == 0 ? n_head_qt : max(0, kt0 - off) / 64;
-            const int n_qt = (lq + 63) / 64 - qt_first;
-            if (n_qt <= 0) continue;
-            const int sp = min(G, (G * n_qt + kSplitTarget - 1) / kSplitTarget);
-            for (int s = 0; s < sp; ++s) {
-                const int g0 = s * G / sp, g1 = (s + 1) * G / sp;
-                i32x4 item = {seg, kt0, g0, g1 - g0};
-                if (sp > 1) first[atomicAdd(&n_first, 1)] = item;
-                else second[atomicAdd(&n_second, 1)] = item;
+    i32x4 *items = (i32x4 *)(wl + 64);
+    // Segments one after the other (their bounds are uniform loads), the key tiles of a segment in parallel.
+    auto for_each_item = [&](auto &&visit) {
+        for (int seg = 0; seg < p.n_segments; ++seg) {
+            const int lq = p.cu_seqlens_q[seg + 1] - p.cu_seqlens_q[seg];
+            const int lk = p.cu_seqlens_k[seg + 1] - p.cu_seqlens_k[seg];
+            const int off = lk - lq;
+            const int n_head_qt = off < 128 ? min((lq + 63) / 64, (128 - off + 63) / 64) : 0;
+            for (int kt0 = threadIdx.x * 128; kt0 < lk; kt0 += (int)blockDim.x * 128) {
+                const int qt_first = kt0 == 0 ? n_head_qt : max(0, kt0 - off) / 64;
+                const int n_qt = (lq + 63) / 64 - qt_first;
+                if (n_qt <= 0) continue;
+                const int sp = min(G, (G * n_qt + kSplitTarget - 1) / kSplitTarget);
+                for (int s = 0; s < sp; ++s) {
+                    const int g0 = s * G / sp, g1 = (s + 1) * G / sp;
+                    visit(i32x4{seg, kt0, g0, g1 - g0}, min((g1 - g0) * n_qt, kDurationBuckets - 1));
+                }
             }
         }
+    };
+    for_each_item([&](i32x4, int duration) { atomicAdd(&bucket[duration], 1); });
+    __syncthreads();
+    if (threadIdx.x == 0) {                          // longest first: slots are handed out from the top bucket down
+        int next = 0;
+        for (int d = kDurationBuckets - 1; d >= 0; --d) {
+            const int n = bucket[d];
+            bucket[d] = next;
+            next += n;
+        }
+        n_items = next;
     }
     __syncthreads();
+    for_each_item([&](i32x4 item, int duration) {
+        const int slot = atomicAdd(&bucket[duration], 1);
+        if (slot < capacity) items[slot] = item;     // (capacity is an upper bound on the item count; see dkv_worklist_capacity)
+    });
+    __syncthreads();
     if (threadIdx.x == 0) {
-        wl[0] = n_first;
-        wl[1] = n_second;
+        wl[0] = min(n_items, capacity);
+        wl[1] = 0;
     }
 }
 __global__ __launch_bounds__(1024) void dkv_worklist_kernel(cf_attn_fwd_params p, int *wl, int capacity)
@@ -145,10 +163,9 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         // flip the order inside the segment to start the heaviest tiles first.
         kt0 = ((loc.len + BKV - 1) / BKV - 1 - loc.tile_in_seg) * BKV;
     } else {
-        const int n_first = wl[0], n_second = wl[1];
-        if (id >= n_first + n_second) return;
+        if (id >= wl[0]) return;
         const i32x4 *items = (const i32x4 *)(wl + 64);
-        const i32x4 item = id < n_first ? items[id] : items[capacity + id - n_first];
+        const i32x4 item = items[id];
         seg = uniform(item[0]);
         kt0 = uniform(item[1]);
         g0 = uniform(item[2]);

@@ -9,7 +9,7 @@ namespace cf {
 // Backward scratch inside the caller's workspace:
 //   delta     [Hq][T] fp32 = rowsum(dO * O)
 //   worklist  bf16 MFMA path only: the dK/dV kernel's work items, written by a small kernel of the same call
-//             (layout in attn_mfma_bwd.hip); worklist_items = capacity of each of its two item arrays
+//             (layout in attn_mfma_bwd.hip); worklist_items = capacity of its item array
 struct BwdWorkspace {
     float *delta;
     int *worklist;
