@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--streams", type=int, default=1, help="HIP streams the dependency groups are dealt over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tile-tables", action="store_true", help="let the kernels search cu_seqlens instead of reading "
+                    "the host-built tile tables (cf_attn_q_tiles)")
     ap.add_argument("--cpu-pairs", type=float, default=3e7, help="unmasked pairs in the oracle's timed sample")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -93,7 +95,8 @@ def main():
         vals = lambda sid, L: inputs.seq_values_device(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"], "cuda:0")
     else:
         vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
-    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams, fused_launch=True).load(vals)
+    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams, fused_launch=True,
+                         tile_tables=not args.no_tile_tables).load(vals)
     pairs = eng.total_pairs
     flop_step = 14.0 * D * Hq * pairs
 
@@ -176,7 +179,7 @@ def main():
            "config": {"workload": args.workload, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "chunk_size": C,
                       "n_sequences": int(len(lens)), "n_chunks": n_chunks, "tokens": int(plan.total_tokens),
                       "unmasked_pairs": int(pairs), "flop_per_step": flop_step, "seed": args.seed,
-                      "plan_build_ms": plan_ms, "streams": args.streams},
+                      "tile_tables": not args.no_tile_tables, "plan_build_ms": plan_ms, "streams": args.streams},
            "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
            "whole_plan_launch": {"ms_per_step": fused_ms, "tflops": flop_step / (fused_ms * 1e-3) / 1e12,
                                  "what": "same step through cf_attn_fwd_batch / cf_attn_bwd_batch"},

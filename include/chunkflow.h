@@ -181,11 +181,38 @@ typedef struct {
     void *o;                            /* device, [T][Hq][D], written                           */
     int64_t o_stride_tok, o_stride_head;
     float *lse;                         /* device, [Hq][T] natural-log sum of exponentials, written */
+    const struct cf_q_tile *q_tiles;    /* device, [n_q_tiles], or NULL (see cf_attn_q_tiles)    */
+    int32_t n_q_tiles;                  /* 0 when q_tiles is NULL                                */
 } cf_attn_fwd_params;
 
+/*
+ * Optional launch order of a chunk (not part of the paper's method; a descriptor like cu_seqlens).  The bf16
+ * head_dim-128 kernels give every 128 query rows of a segment to one workgroup per head, and the work of such
+ * a tile grows with its position in the sequence.  Workgroups start in grid order, so the order decides how
+ * well the last ones fill the machine.  Without a table each workgroup finds its tile by searching
+ * cu_seqlens (tiles of the last segment first); with one, workgroup rank r takes q_tiles[r]: the tiles of the
+ * whole chunk sorted by the number of keys they read, longest first, each with its segment's bounds so that
+ * the kernel reads one 32-byte record instead of searching.
+ * cf_attn_q_tiles builds the table on the HOST from host copies of cu_seqlens (it depends only on the chunk's
+ * geometry: build it once per plan, upload it, pass the device pointer).  Like cu_seqlens the device copy is
+ * not validated.  The scalar kernels ignore it.
+ *   out       host, [capacity] records, or NULL to only count
+ *   returns   the number of tiles = sum over segments of ceil(Lq_g / 128), or CF_EINVAL (NULL cu arrays,
+ *             n_segments < 1, a segment with Lq < 1 or Lk < Lq, capacity too small for a non-NULL out)
+ */
+typedef struct cf_q_tile {
+    int32_t q_begin, q_len;             /* the segment's query rows: cu_seqlens_q[g], Lq_g       */
+    int32_t k_begin, k_len;             /* the segment's key rows:   cu_seqlens_k[g], Lk_g       */
+    int32_t tile;                       /* this tile covers rows [128*tile, 128*tile+128) of the segment */
+    int32_t segment;                    /* g                                                     */
+    int32_t reserved[2];
+} cf_q_tile;
+int64_t cf_attn_q_tiles(const int32_t *cu_seqlens_q_host, const int32_t *cu_seqlens_k_host, int32_t n_segments,
+                        cf_q_tile *out, int64_t capacity);
+
 /* Enqueue the forward pass.  Errors: NULL pointers, sizes < 1, n_kv_tokens < n_tokens,
- * Hq % Hkv != 0, misaligned base pointers or strides (bf16: multiples of 8 elements, fp32: of 4)
- * -> CF_EINVAL; head_dim / dtype not built -> CF_EUNSUPPORTED; launch failure -> CF_EHIP. */
+ * Hq % Hkv != 0, misaligned base pointers or strides (bf16: multiples of 8 elements, fp32: of 4),
+ * q_tiles without a plausible n_q_tiles (or the reverse) -> CF_EINVAL; head_dim / dtype not built -> CF_EUNSUPPORTED; launch failure -> CF_EHIP. */
 int cf_attn_fwd(const cf_attn_fwd_params *p, void *hip_stream);
 
 /*

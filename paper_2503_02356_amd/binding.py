@@ -18,7 +18,7 @@ CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
 CF_PLAN_MERGE_TAILS = 1
 
-EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_build_chunks_ex", "cf_plan_free", "cf_plan_get",
+EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_build_chunks_ex", "cf_attn_q_tiles", "cf_plan_free", "cf_plan_get",
            "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_attn_fwd_batch", "cf_attn_bwd_batch",
            "cf_count_pairs", "cf_profile_next_call"]
 
@@ -57,7 +57,7 @@ class AttnFwdParams(C.Structure):
                 ("q", C.c_void_p), ("q_stride_tok", C.c_int64), ("q_stride_head", C.c_int64),
                 ("k", C.c_void_p), ("v", C.c_void_p), ("kv_stride_tok", C.c_int64), ("kv_stride_head", C.c_int64),
                 ("o", C.c_void_p), ("o_stride_tok", C.c_int64), ("o_stride_head", C.c_int64),
-                ("lse", C.c_void_p)]
+                ("lse", C.c_void_p), ("q_tiles", C.c_void_p), ("n_q_tiles", C.c_int32)]
 
 
 class AttnBwdParams(C.Structure):
@@ -97,6 +97,8 @@ def lib():
         L.cf_profile_next_call.argtypes = [C.c_void_p, C.c_void_p]
         L.cf_count_pairs.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         L.cf_count_pairs.restype = C.c_int64
+        L.cf_attn_q_tiles.restype = C.c_int64
+        L.cf_attn_q_tiles.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64]
         _lib = L
     return _lib
 
@@ -214,9 +216,22 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_fwd_params(q, k, v, o, lse, cu_q, cu_k, scale, flags=0):
+def cf_attn_q_tiles(cu_q, cu_k):
+    """Host table of the chunk's 128-row query tiles, heaviest first: int32 array [n_tiles, 8] with the columns
+    of cf_q_tile (q_begin, q_len, k_begin, k_len, tile, segment, 0, 0).  cu_q, cu_k: host int arrays."""
+    a = np.ascontiguousarray(cu_q, dtype=np.int32)
+    b = np.ascontiguousarray(cu_k, dtype=np.int32)
+    n = _check(lib().cf_attn_q_tiles(a.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p), len(a) - 1, None, 0))
+    out = np.zeros((n, 8), dtype=np.int32)
+    _check(lib().cf_attn_q_tiles(a.ctypes.data_as(C.c_void_p), b.ctypes.data_as(C.c_void_p), len(a) - 1,
+                                 out.ctypes.data_as(C.c_void_p), n))
+    return out
+
+
+def make_fwd_params(q, k, v, o, lse, cu_q, cu_k, scale, flags=0, q_tiles=None):
     """q,o [T,Hq,D]; k,v [Tk,Hkv,D] (views with the same strides); lse [Hq,T] fp32 contiguous;
-    cu_q, cu_k int32 device tensors [n_seg+1]."""
+    cu_q, cu_k int32 device tensors [n_seg+1]; q_tiles: optional int32 device tensor [n_tiles, 8], the
+    uploaded result of cf_attn_q_tiles for the same cu_seqlens."""
     T, Hq, D = q.shape
     Tk, Hkv, _ = k.shape
     assert q.is_cuda and q.stride(2) == 1 and k.stride(2) == 1 and v.stride() == k.stride() and o.stride(2) == 1
@@ -231,9 +246,12 @@ def make_fwd_params(q, k, v, o, lse, cu_q, cu_k, scale, flags=0):
     p.k, p.v, p.kv_stride_tok, p.kv_stride_head = k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1)
     p.o, p.o_stride_tok, p.o_stride_head = o.data_ptr(), o.stride(0), o.stride(1)
     p.lse = lse.data_ptr()
+    if q_tiles is not None:
+        assert q_tiles.is_cuda and q_tiles.is_contiguous() and q_tiles.element_size() == 4 and q_tiles.shape[1] == 8
+        p.q_tiles, p.n_q_tiles = q_tiles.data_ptr(), q_tiles.shape[0]
     # The struct only carries raw addresses: keep the tensors alive as long as it lives, or the allocator may
     # hand their memory (e.g. a temporary cu_seqlens tensor) to someone else before the kernels have read it.
-    p._keepalive = (q, k, v, o, lse, cu_q, cu_k)
+    p._keepalive = (q, k, v, o, lse, cu_q, cu_k, q_tiles)
     return p
 
 

@@ -45,6 +45,13 @@ int check_fwd(const cf_attn_fwd_params *p, const char *who, bool sizes_only)
     if (!aligned(p->q, 16) || !aligned(p->k, 16) || !aligned(p->v, 16) || !aligned(p->o, 16) ||
         !aligned(p->lse, 4) || !aligned(p->cu_seqlens_q, 4) || !aligned(p->cu_seqlens_k, 4))
         return cf::fail(CF_EINVAL, "%s: q, k, v, o must be 16-byte aligned", who);
+    // the optional tile table: between ceil(T / 128) and T / 128 + n_segments records of 32 bytes
+    if ((p->q_tiles == nullptr) != (p->n_q_tiles == 0) || p->n_q_tiles < 0 || !aligned(p->q_tiles, 16))
+        return cf::fail(CF_EINVAL, "%s: q_tiles / n_q_tiles = %d do not go together (NULL with 0, 16-byte aligned)", who,
+                        p->n_q_tiles);
+    if (p->q_tiles && (p->n_q_tiles < (p->n_tokens + 127) / 128 || p->n_q_tiles > p->n_tokens / 128 + p->n_segments))
+        return cf::fail(CF_EINVAL, "%s: n_q_tiles = %d cannot be the tile count of %d tokens in %d segments", who,
+                        p->n_q_tiles, p->n_tokens, p->n_segments);
     return CF_OK;
 }
 

@@ -519,6 +519,10 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
         if (seg >= p.n_segments) return;
         q_seg0 = p.cu_seqlens_q[seg], lq = p.cu_seqlens_q[seg + 1] - q_seg0;
         k_seg0 = p.cu_seqlens_k[seg], lk = p.cu_seqlens_k[seg + 1] - k_seg0;
+    } else if (p.q_tiles != nullptr) {
+        if (rank >= p.n_q_tiles) return;
+        const QTile t = read_q_tile(p.q_tiles, rank);
+        tile_in_seg = t.tile_in_seg, q_seg0 = t.q_begin, lq = t.q_len, k_seg0 = t.k_begin, lk = t.k_len;
     } else {
         TileLocation loc;
         if (!locate_tile(p.cu_seqlens_q, p.cu_seqlens_k, p.n_segments, BM, rank, loc)) return;
@@ -738,7 +742,7 @@ BwdShape bwd_shape(const cf_attn_fwd_params &p, const BwdWorkspace &ws)
     BwdShape g;
     // Upper bounds on tile counts: sum_g ceil(L_g / tile) <= total / tile + n_segments.
     const int64_t kv_tiles = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
-    const int64_t q_tiles = (int64_t)p.n_tokens / BM + p.n_segments;
+    const int64_t q_tiles = p.q_tiles ? (int64_t)p.n_q_tiles : (int64_t)p.n_tokens / BM + p.n_segments;
     // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
     g.fused = kv_tiles * p.n_kv_heads >= 4096;
     g.dq_blocks = q_tiles * p.n_q_heads;

@@ -37,11 +37,18 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
     const int h = kh * G + id % G;
     const int rank = id / G;
 
-    TileLocation loc;
-    if (!locate_tile(p.cu_seqlens_q, p.cu_seqlens_k, p.n_segments, BM, rank, loc)) return;
-    // (the same in every lane, but values that leave the search loop do not look that way to the compiler)
-    const int tile_in_seg = uniform(loc.tile_in_seg);
-    const int q_seg0 = uniform(loc.begin), lq = uniform(loc.len), k_seg0 = uniform(loc.other_begin), lk = uniform(loc.other_len);
+    int tile_in_seg, q_seg0, lq, k_seg0, lk;
+    if (p.q_tiles != nullptr) {
+        if (rank >= p.n_q_tiles) return;
+        const QTile t = read_q_tile(p.q_tiles, rank);
+        tile_in_seg = t.tile_in_seg, q_seg0 = t.q_begin, lq = t.q_len, k_seg0 = t.k_begin, lk = t.k_len;
+    } else {
+        TileLocation loc;
+        if (!locate_tile(p.cu_seqlens_q, p.cu_seqlens_k, p.n_segments, BM, rank, loc)) return;
+        // (the same in every lane, but values that leave the search loop do not look that way to the compiler)
+        tile_in_seg = uniform(loc.tile_in_seg);
+        q_seg0 = uniform(loc.begin), lq = uniform(loc.len), k_seg0 = uniform(loc.other_begin), lk = uniform(loc.other_len);
+    }
     const int off = lk - lq;                         // prefix keys every row of the segment sees
     const int q_tile0 = tile_in_seg * BM;
     const int rows_valid = min(BM, lq - q_tile0);
@@ -208,7 +215,10 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_batch_kernel(FwdBatch b)
 }
 
 // Upper bound on the number of 128-row tiles: sum_g ceil(Lq_g / BM) <= T / BM + n_segments.
-int64_t fwd_blocks(const cf_attn_fwd_params &p) { return ((int64_t)p.n_tokens / BM + p.n_segments) * p.n_q_heads; }
+int64_t fwd_blocks(const cf_attn_fwd_params &p)
+{
+    return (p.q_tiles ? (int64_t)p.n_q_tiles : (int64_t)p.n_tokens / BM + p.n_segments) * p.n_q_heads;
+}
 
 }  // namespace
 

@@ -175,6 +175,18 @@ __device__ __forceinline__ T *uniform(T *p)
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ void wait_lds_dma() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
+// The 128-row query tile of workgroup rank `rank` from the caller's table (cf_attn_q_tiles: heaviest tile first,
+// each record carries its segment's bounds): one uniform 32-byte read instead of the search of locate_tile.
+struct QTile {
+    int tile_in_seg, q_begin, q_len, k_begin, k_len;
+};
+__device__ __forceinline__ QTile read_q_tile(const cf_q_tile *table, int rank)
+{
+    const i32x4 *rec = (const i32x4 *)(table + rank);
+    const i32x4 a = rec[0], b = rec[1];
+    return QTile{uniform(b[0]), uniform(a[0]), uniform(a[1]), uniform(a[2]), uniform(a[3])};
+}
+
 // Stores a wavefront's 32 x 128 block of bf16 results (computed transposed: a lane owns one ROW, register group
 // (j, g4) of acc holds its 4 consecutive d starting at 32*j + 8*g4 + 4*half) to global rows of 256 bytes.
 // A direct store would write 8-byte pieces of 32 different rows per instruction (64 cache lines touched per

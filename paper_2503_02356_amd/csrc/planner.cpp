@@ -321,5 +321,42 @@ extern "C" int64_t cf_count_pairs(const int32_t *cu_q, const int32_t *cu_k, int3
     return pairs;
 }
 
+extern "C" int64_t cf_attn_q_tiles(const int32_t *cu_q, const int32_t *cu_k, int32_t n_segments, cf_q_tile *out,
+                                   int64_t capacity)
+{
+    if (!cu_q || !cu_k || n_segments < 1) return cf::fail(CF_EINVAL, "cf_attn_q_tiles: bad argument");
+    constexpr int64_t kRows = 128, kKeysPerStep = 64;
+    int64_t n_tiles = 0;
+    for (int32_t g = 0; g < n_segments; ++g) {
+        const int64_t lq = cu_q[g + 1] - cu_q[g], lk = cu_k[g + 1] - cu_k[g];
+        if (lq < 1 || lk < lq) return cf::fail(CF_EINVAL, "cf_attn_q_tiles: segment %d has Lq=%lld Lk=%lld", g,
+                                               (long long)lq, (long long)lk);
+        n_tiles += (lq + kRows - 1) / kRows;
+    }
+    if (!out) return n_tiles;
+    if (capacity < n_tiles) return cf::fail(CF_EINVAL, "cf_attn_q_tiles: capacity %lld < %lld tiles", (long long)capacity,
+                                            (long long)n_tiles);
+    try {
+        std::vector<std::pair<int64_t, int64_t>> order;   // (-steps, index): ascending pairs = longest first, then list order
+        order.reserve((size_t)n_tiles);
+        int64_t n = 0;
+        for (int32_t g = 0; g < n_segments; ++g) {
+            const int64_t lq = cu_q[g + 1] - cu_q[g], lk = cu_k[g + 1] - cu_k[g];
+            for (int64_t t = 0; t * kRows < lq; ++t, ++n) {
+                const int64_t keys = std::min((t + 1) * kRows, lq) + (lk - lq);   // keys the tile's last row sees
+                order.push_back({-((keys + kKeysPerStep - 1) / kKeysPerStep), n});
+                out[n] = cf_q_tile{cu_q[g], (int32_t)lq, cu_k[g], (int32_t)lk, (int32_t)t, g, {0, 0}};
+            }
+        }
+        std::sort(order.begin(), order.end());
+        std::vector<cf_q_tile> sorted((size_t)n_tiles);
+        for (int64_t i = 0; i < n_tiles; ++i) sorted[(size_t)i] = out[order[(size_t)i].second];
+        std::copy(sorted.begin(), sorted.end(), out);
+    } catch (const std::bad_alloc &) {
+        return cf::fail(CF_ENOMEM, "cf_attn_q_tiles: out of host memory");
+    }
+    return n_tiles;
+}
+
 extern "C" const char *cf_last_error(void) { return cf::g_err; }
 extern "C" int cf_version(void) { return 100; }

@@ -26,7 +26,7 @@ def schedule_memory(plan, K, n_q_heads, n_kv_heads, head_dim, elem_bytes=2):
 
 class ChunkAttention:
     def __init__(self, plan, n_q_heads, n_kv_heads, head_dim, dtype, scale=None, device="cuda:0", flags=0,
-                 n_streams=1, fused_launch=False, only_groups=None):
+                 n_streams=1, fused_launch=False, only_groups=None, tile_tables=True):
         """n_streams > 1: dependency groups are dealt over that many HIP streams (default priority), so that
         the last, partly filled wave of workgroups of one chunk's kernel overlaps with the next group's
         kernels.  The chunks of one group stay on one stream, in the order of section 4.2."""
@@ -35,6 +35,9 @@ class ChunkAttention:
         # fused_launch: run_forward / run_backward hand the whole plan to cf_attn_fwd_batch / cf_attn_bwd_batch
         # (one workspace per chunk); otherwise one cf_attn_fwd / cf_attn_bwd call per chunk.
         self.fused_launch = bool(fused_launch)
+        # tile_tables: give every chunk's calls the table of cf_attn_q_tiles (built on the host when the plan is
+        # placed: it only depends on the chunk's cu_seqlens), so that the kernels start their heaviest tiles first
+        self.tile_tables = bool(tile_tables)
         self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.scale = float(scale) if scale is not None else 1.0 / float(np.sqrt(head_dim))
         self.dev, self.flags = torch.device(device), flags
@@ -161,8 +164,10 @@ class ChunkAttention:
                 ch["cu_k_host"] = cu.copy()
             ch["cu_k"] = torch.from_numpy(ch["cu_k_host"].copy()).to(dev)
             ch["pairs"] = B.cf_count_pairs(ch["cu_q_host"], ch["cu_k_host"])
+            if self.tile_tables:
+                ch["q_tiles"] = torch.from_numpy(B.cf_attn_q_tiles(ch["cu_q_host"], ch["cu_k_host"])).to(dev)
             ch["fwd"] = B.make_fwd_params(ch["q"], ch["k"], ch["v"], ch["o"], ch["lse"], ch["cu_q"], ch["cu_k"],
-                                          self.scale, self.flags)
+                                          self.scale, self.flags, q_tiles=ch.get("q_tiles"))
             ws_bytes = max(ws_bytes, B.cf_attn_bwd_workspace_bytes(ch["fwd"]))
             self.chunks.append(ch)
         # one backward workspace per stream: calls on different streams overlap

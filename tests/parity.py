@@ -42,12 +42,12 @@ def check(got, ref, dtype, what=""):
 
 
 def run_gpu(lens, C, Hq, Hkv, D, dtype, seed, flags=0, K=None, scale=None, fused_launch=False, n_streams=1,
-            merge_tails=False):
+            merge_tails=False, tile_tables=True):
     """Chunk-plan the lengths with the library, run forward+backward on the GPU, return per-sequence results."""
     plan = B.cf_build_chunks_ex(lens, C, B.CF_PLAN_MERGE_TAILS) if merge_tails else B.cf_build_chunks(lens, C)
     vals = lambda sid, L: inputs.seq_values(seed, sid, lens[sid], Hq, Hkv, D, dtype)
     eng = ChunkAttention(plan, Hq, Hkv, D, dtype, scale=scale, flags=flags, fused_launch=fused_launch,
-                         n_streams=n_streams).load(vals)
+                         n_streams=n_streams, tile_tables=tile_tables).load(vals)
     if K is None:
         eng.run_forward()
         eng.run_backward()

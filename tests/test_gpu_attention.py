@@ -91,6 +91,22 @@ def test_merged_tails_plan(dtype, D, flags, K, fused):
     P.check(got, ref, dtype, f"merged tails {dtype} D={D} flags={flags} K={K} fused={fused}")
 
 
+@pytest.mark.parametrize("merge_tails", [False, True])
+def test_tile_table_and_on_device_search_give_the_same_result(merge_tails):
+    """With the host-built tile table (the runner's default) and without it (the kernels search cu_seqlens) the
+    forward and dQ kernels do the same work in a different order: O, LSE and dQ must be bitwise equal, and both
+    must match the oracle."""
+    lens = [700, 40, 300, 33, 1000, 129, 64, 5, 450, 17, 260, 90, 128, 256]
+    a, _ = P.run_gpu(lens, 256, 4, 2, 128, "bf16", seed=13, merge_tails=merge_tails, tile_tables=True)
+    b, _ = P.run_gpu(lens, 256, 4, 2, 128, "bf16", seed=13, merge_tails=merge_tails, tile_tables=False)
+    for sid in a:
+        for name in ("o", "lse", "dq"):
+            assert np.array_equal(a[sid][name], b[sid][name]), (sid, name)
+    ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=13)
+    P.check(a, ref, "bf16", "with tile tables")
+    P.check(b, ref, "bf16", "without tile tables")
+
+
 def test_recompute_schedule_gives_same_result():
     """Algorithm 2 with K=1: the first N-1 chunks run forward twice; results must not change."""
     lens = [900, 40, 300]

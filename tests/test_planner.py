@@ -133,6 +133,18 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu():
     assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL          # NULL pointers
     assert b"NULL" in B.lib().cf_last_error()
     assert B.cf_attn_bwd_workspace_bytes(p) >= 4 * 16 * 4
+    # a tile table needs a plausible record count, and a count needs a table (fake, aligned addresses: the
+    # checks run on the host and nothing is dereferenced)
+    for name in ("cu_seqlens_q", "cu_seqlens_k", "q", "k", "v", "o", "lse"):
+        setattr(p, name, 0x1000)
+    p.softmax_scale, p.q_stride_tok, p.q_stride_head, p.kv_stride_tok, p.kv_stride_head = 1.0, 512, 128, 256, 128
+    p.o_stride_tok, p.o_stride_head = 512, 128
+    p.q_tiles, p.n_q_tiles = 0x2000, 0
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL and b"q_tiles" in B.lib().cf_last_error()
+    p.q_tiles, p.n_q_tiles = 0, 1
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL and b"q_tiles" in B.lib().cf_last_error()
+    p.q_tiles, p.n_q_tiles = 0x2000, 3                                         # 16 tokens in 1 segment: exactly 1 tile
+    assert B.lib().cf_attn_fwd(ctypes.byref(p), None) == B.CF_EINVAL and b"n_q_tiles" in B.lib().cf_last_error()
     b = B.AttnBwdParams()
     assert B.lib().cf_attn_bwd(None, None) == B.CF_EINVAL
     assert B.lib().cf_attn_bwd(ctypes.byref(b), None) < 0
@@ -187,3 +199,28 @@ def test_batch_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.cf_attn_fwd_batch(arr, 2, None) == B.CF_EINVAL and b"NULL" in L.cf_last_error()
     arr[1].head_dim = 96
     assert L.cf_attn_fwd_batch(arr, 2, None) in (B.CF_EINVAL, B.CF_EUNSUPPORTED)
+
+
+def test_q_tile_table_lists_every_tile_heaviest_first():
+    """cf_attn_q_tiles against a direct enumeration: every 128-row tile of every segment exactly once, with its
+    segment's bounds, ordered by the number of 64-key steps its last row needs (ties: segment, then tile)."""
+    rng = np.random.default_rng(3)
+    for trial in range(200):
+        n = int(rng.integers(1, 12))
+        lq = rng.integers(1, 700, size=n)
+        prefix = rng.integers(0, 2, size=n) * rng.integers(0, 900, size=n)
+        cu_q = np.concatenate([[0], np.cumsum(lq)])
+        cu_k = np.concatenate([[0], np.cumsum(lq + prefix)])
+        rows = []
+        for g in range(n):
+            for j in range(-(-int(lq[g]) // 128)):
+                keys = min((j + 1) * 128, int(lq[g])) + int(prefix[g])
+                rows.append((-(-(-keys // 64)) * -1, len(rows), int(cu_q[g]), int(lq[g]), int(cu_k[g]), int(lq[g] + prefix[g]), j, g))
+        rows = sorted((-steps, i, *rest) for (steps, i, *rest) in rows)
+        want = np.array([r[2:] + (0, 0) for r in rows], dtype=np.int32).reshape(-1, 8)
+        got = B.cf_attn_q_tiles(cu_q, cu_k)
+        assert np.array_equal(got, want), trial
+    with pytest.raises(B.CfError):
+        B.cf_attn_q_tiles([0, 4, 4], [0, 4, 4])             # empty segment
+    with pytest.raises(B.CfError):
+        B.cf_attn_q_tiles([0, 4], [0, 3])                   # fewer keys than queries
