@@ -65,7 +65,7 @@ static_assert(DKV_STAGE_BYTES >= 4 * 2 * EXCH_SLOT_BYTES, "exchange area too sma
 constexpr int kSplitTarget = 48;
 constexpr int kDurationBuckets = 256;
 
-// Runs in ONE workgroup of any size: as a kernel of its own (whole-plan launches) or as the last workgroup of the dQ
+// Runs in ONE workgroup of any size: as a kernel of its own (whole-plan launches) or as the first workgroup of the dQ
 // launch, which the dK/dV kernel follows anyway (no launch of its own on the per-chunk path).
 __device__ __forceinline__ void build_dkv_worklist(const cf_attn_fwd_params &p, int *wl, int capacity)
 {
@@ -692,11 +692,13 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
 }
 
 // Blocks [0, head_blocks) do the head tiles (one per (segment, head)), the others the main work.
-// wl != nullptr: the launch has one extra workgroup (the last) that builds the dK/dV work list.
+// wl != nullptr: the launch has one extra workgroup (the first) that builds the dK/dV work list.
 __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, float *__restrict__ delta, int head_blocks,
                                                          int *wl, int capacity)
 {
-    if (wl != nullptr && blockIdx.x == gridDim.x - 1) {
+    // The list builder is workgroup 0: it starts with the first wave of workgroups and is long done when the
+    // launch ends (as the last workgroup it would start last and could be what the launch ends with).
+    if (wl != nullptr && blockIdx.x == 0) {
         build_dkv_worklist(b.f, wl, capacity);
         return;
     }
@@ -704,7 +706,7 @@ __global__ __launch_bounds__(256, 2) void mfma_dq_kernel(cf_attn_bwd_params b, f
     // loads of the next tile cannot alias the reads of the current one, or it waits for them too early.
     __shared__ __attribute__((aligned(16))) char stage_a[DQ_STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) char stage_b[DQ_STAGE_BYTES];
-    const int id = blockIdx.x;
+    const int id = (int)blockIdx.x - (wl != nullptr ? 1 : 0);
     const bool head = id < head_blocks;   // a run-time flag, uniform over the workgroup: one code path, one register allocation
     dq_body(b, delta, head ? id : id - head_blocks, head, stage_a, stage_b);
 }
@@ -794,7 +796,7 @@ hipError_t launch_mfma_bwd(const cf_attn_bwd_params &b, const BwdWorkspace &ws, 
     if (!g.ok) return hipErrorInvalidConfiguration;
     hipError_t e;
     // dQ first: it also produces delta (main blocks: <dO, O>; head blocks: the exact sum for the head rows), which
-    // the dK/dV kernel reads; its last workgroup builds the dK/dV work list where one is needed.
+    // the dK/dV kernel reads; its first workgroup builds the dK/dV work list where one is needed.
     int *wl = g.fused ? nullptr : ws.worklist;
     mfma_dq_kernel<<<dim3((unsigned)(g.dq_blocks + g.head_dq + (wl ? 1 : 0))), 256, 0, s>>>(b, ws.delta, g.head_dq, wl,
                                                                                              (int)ws.worklist_items);
