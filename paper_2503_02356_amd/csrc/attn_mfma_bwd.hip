@@ -4,25 +4,27 @@
 //
 // Two kernels, no dQ atomics:
 //
-//  dkv kernel  A workgroup (4 wavefronts) owns 128 consecutive key rows of one segment; each wavefront owns
-//              32 of them and keeps their dK^T and dV^T (fp32, 128 registers) for the whole kernel.  It
-//              loops over the 64-row query tiles that can see its keys; Q and dO tiles are staged through
-//              LDS (double buffered, XOR-swizzled so that row reads and transposing reads are both free
-//              of bank conflicts).  Per tile and wavefront:
-//                  S = Q K_w^T          dP = dO V_w^T           (A from LDS rows, B = K_w / V_w registers)
-//                  P = exp2(S c - LSE)  dS = P (dP - delta)
-//                  dV_w^T += dO^T P     dK_w^T += Q^T dS        (A by transposing LDS reads, B registers)
-//              FUSED_HEADS = true : the workgroup also loops over the query heads of its key/value head
-//                  and is the only writer of its dK/dV rows (plain read-modify-write, bitwise
+//  dkv kernel  A workgroup (8 wavefronts) owns 128 consecutive key rows of one segment.  Wavefronts w and w + 4
+//              own the same 32 of them: one keeps their dV^T, the other their dK^T (fp32, 64 registers each)
+//              for the whole kernel.  The workgroup loops over the 64-row query tiles that can see its keys, for
+//              one or several query heads of its key/value head; Q and dO tiles go straight from global memory
+//              into a ring of three XOR-swizzled LDS stages (row reads and transposing reads are both free of
+//              bank conflicts).  Per 32-row block of queries:
+//                  role 0:  S = Q K_w^T          P = exp2(S c - LSE)  -> LDS       dV_w^T += dO^T P
+//                  role 1:  dP = dO V_w^T        dS = P (dP - delta)               dK_w^T += Q^T dS
+//              (A operands from LDS rows resp. transposing LDS reads, B operands K_w / V_w / P / dS in registers).
+//              FUSED_HEADS = true : one workgroup per key tile and key/value head loops over ALL query heads
+//                  of the group and is the only writer of its dK/dV rows (plain read-modify-write, bitwise
 //                  reproducible).  Used when the launch has enough key tiles to fill the GPU.
-//              FUSED_HEADS = false: one workgroup per (key tile, query head), 7x..8x more workgroups for
-//                  short chunks; the heads of a group meet in dK/dV through fp32 atomic adds (once per
-//                  workgroup, at the end).
+//              FUSED_HEADS = false: a work list built on the device cuts the (key tile, query heads) work into
+//                  items of similar length, longest first; the items of one key/value head meet in dK/dV
+//                  through fp32 atomic adds (once per workgroup, at the end).
 //
 //  dq kernel   Same shape as the forward kernel: a workgroup owns 128 query rows of one head, key/value
 //              tiles of 64 rows go through LDS, everything transposed so that a lane owns one query:
 //                  S^T = K Q^T   dP^T = V dO^T   dS^T = P^T (dP^T - delta)   dQ^T += K^T dS^T
 //              LSE and delta are one scalar per lane; dS^T feeds the last product straight from registers.
+//              It also computes delta = <dO, O> (which the dK/dV kernel, launched after it, reads).
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
