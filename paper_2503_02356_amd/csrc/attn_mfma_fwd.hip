@@ -3,7 +3,8 @@
 //
 // One workgroup = 4 wavefronts = 128 consecutive query rows of one segment and one query head; each
 // wavefront owns 32 rows.  Key/value tiles of 64 rows are copied straight from global memory into LDS
-// (global_load_lds, double buffered, XOR-swizzled rows) and shared by the four wavefronts.  Everything is computed TRANSPOSED so that a lane owns one query:
+// (buffer loads with an LDS destination, double buffered, XOR-swizzled rows) and shared by the four wavefronts.
+// Everything is computed TRANSPOSED so that a lane owns one query:
 //     S^T = K Q^T   (A = K tile rows from LDS, B = Q^T kept in registers for the whole kernel)
 //     O^T += V^T P^T (A = V^T through transposing LDS reads, B = P^T straight from the S^T registers)
 // With the query on the lane axis the row maximum and row sum are in-lane reductions plus one exchange
