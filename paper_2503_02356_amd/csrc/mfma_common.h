@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "chunkflow.h"
+
 namespace cf {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
