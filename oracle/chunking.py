@@ -3,6 +3,13 @@
 Follows the paper's Algorithm 1 (section 4.1) and Algorithm 2 (section 4.2) step by step.  Where the
 paper leaves a choice open the reading is stated at the step that takes it.
 
+Pins: the paper's worked examples (lengths {1,1,2,4} Units with ChunkSize 2 and 4 Units give 4 and 2 chunks),
+validity invariants on random lists, exhaustive minimum bin counts on tiny inputs, and the counts
+section 4.2 states for Algorithm 2.  PARITY UNPINNED by the paper: WHICH valid packing Algorithm 1's
+'try binpacking' step produces (the paper names no heuristic and prints no packing), and the whole
+merge_tails variant (the paper prints no such chunking); both are pinned only by those invariants and by
+hand-worked examples of the reading taken here.
+
 A chunk is a dict:
     tokens      number of tokens in the chunk (<= chunk_size)
     prefix_len  tokens of the same long sequence that lie in earlier chunks (0 for packed chunks
