@@ -26,6 +26,8 @@ def main():
     ap.add_argument("--tokens-per-round", type=int, default=1_500_000)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--max-rounds", type=int, default=0, help="stop after this many rounds (0: the whole batch)")
+    ap.add_argument("--merge-tails", action="store_true", help="plan with CF_PLAN_MERGE_TAILS: the last, partial slice of a "
+                    "split sequence shares a chunk with short sequences")
     args = ap.parse_args()
 
     import torch
@@ -39,7 +41,7 @@ def main():
     Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
     lens, C = inputs.seq_lens("longtail_16k", args.seed, None)
     t0 = time.perf_counter()
-    plan = B.cf_build_chunks(lens, C)
+    plan = B.cf_build_chunks_ex(lens, C, B.CF_PLAN_MERGE_TAILS) if args.merge_tails else B.cf_build_chunks(lens, C)
     plan_ms = (time.perf_counter() - t0) * 1e3
     vals = lambda sid, L: inputs.seq_values_device(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"], "cuda:0")
 
@@ -88,7 +90,8 @@ def main():
                                  "chunk_size": C, "n_sequences": int(len(lens)), "n_chunks": int(plan.n_chunks),
                                  "tokens": total_tokens, "unmasked_pairs": int(total_pairs), "flop": flop,
                                  "plan_build_ms": plan_ms, "rounds": len(rounds),
-                                 "tokens_per_round": args.tokens_per_round, "seed": args.seed},
+                                 "tokens_per_round": args.tokens_per_round, "merge_tails": args.merge_tails,
+                                 "seed": args.seed},
                       "pct_of_bf16_mfma_peak": 100.0 * flop / (total_ms * 1e-3) / 1e12 / 2516.6,
                       "per_round": per_round}), flush=True)
 
