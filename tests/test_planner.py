@@ -224,3 +224,13 @@ def test_q_tile_table_lists_every_tile_heaviest_first():
         B.cf_attn_q_tiles([0, 4, 4], [0, 4, 4])             # empty segment
     with pytest.raises(B.CfError):
         B.cf_attn_q_tiles([0, 4], [0, 3])                   # fewer keys than queries
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    """The binding has no other path than the built library: without it every call raises."""
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libchunkflow.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        B.cf_build_chunks([3, 4], 4)
+    with pytest.raises(RuntimeError, match="missing"):
+        B.cf_attn_fwd(B.AttnFwdParams(), None)
