@@ -140,6 +140,12 @@ def main():
     part_reps = max(1, min(args.steps, 5))
     step(fused=True)                                   # warm-up of the whole-plan launch
     fused_ms = wall_ms(lambda: step(fused=True), part_reps)
+    graph_ms = None
+    if args.streams == 1:                              # the same step recorded once into a HIP graph and replayed
+        graph = eng.capture_step()
+        graph.replay()
+        graph_ms = wall_ms(graph.replay, part_reps)
+        del graph
     fwd_pass_ms = wall_ms(eng.run_forward, part_reps)
     bwd_pass_ms = wall_ms(bwd_pass, part_reps)
 
@@ -183,6 +189,8 @@ def main():
            "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
            "whole_plan_launch": {"ms_per_step": fused_ms, "tflops": flop_step / (fused_ms * 1e-3) / 1e12,
                                  "what": "same step through cf_attn_fwd_batch / cf_attn_bwd_batch"},
+           "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "tflops": flop_step / (graph_ms * 1e-3) / 1e12,
+                                                           "what": "the per-chunk step captured in a HIP graph, one replay per step"},
            "fwd_only": {"ms": fwd_pass_ms, "tflops": 4.0 * D * Hq * pairs / (fwd_pass_ms * 1e-3) / 1e12},
            "bwd_only": {"ms": bwd_pass_ms, "tflops": 10.0 * D * Hq * pairs / (bwd_pass_ms * 1e-3) / 1e12,
                         "includes": "zeroing of the dK/dV buffers"},

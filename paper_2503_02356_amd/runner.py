@@ -246,6 +246,23 @@ class ChunkAttention:
         what later chunks need) and run forward again right before their backward."""
         self._launch((op == B.CF_OP_BWD, c) for op, c in self.plan.schedule(K) if self.chunks[c] is not None)
 
+    def capture_step(self, K=None):
+        """One whole step (zeroing of the gradients, forward, backward; Algorithm 2 with K kept chunks when K is
+        given) recorded into a HIP graph and returned: `graph.replay()` then re-issues it with one call.  The
+        entry points suit capture as they are: they only enqueue kernels on the stream they are given -- no
+        allocation, no synchronisation, no memset node (the gradients are cleared by a fill kernel).  Single
+        stream only."""
+        assert not self.streams, "capture_step records the single-stream launch order"
+        step = (lambda: self.run_schedule(K)) if K is not None else (lambda: (self.run_forward(), self.run_backward()))
+        self.zero_grads()
+        step()                                   # every lazy initialisation happens outside the capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.zero_grads()
+            step()
+        return graph
+
     # ------------------------------------------------------------------ results
     def results(self):
         """Per input sequence: o, lse, dq, dk, dv as fp64 numpy arrays (re-indexed through the plan)."""

@@ -9,6 +9,7 @@ import torch
 from oracle import attention as OA
 from paper_2503_02356_amd import binding as B
 from paper_2503_02356_amd import inputs
+from paper_2503_02356_amd.runner import ChunkAttention
 from tests import parity as P
 
 pytestmark = pytest.mark.gpu
@@ -105,6 +106,38 @@ def test_tile_table_and_on_device_search_give_the_same_result(merge_tails):
     ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=13)
     P.check(a, ref, "bf16", "with tile tables")
     P.check(b, ref, "bf16", "without tile tables")
+
+
+@pytest.mark.parametrize("K", [None, 1])
+def test_step_captured_in_a_hip_graph_replays_correctly(K):
+    """A whole step recorded into a HIP graph: every replay, with eager work of the same engine and
+    synchronisations in between, must reproduce the eager results (forward and dQ bitwise; dK/dV, summed by
+    atomics, within the tolerance against the oracle)."""
+    lens = [700, 40, 300, 33, 1000, 129, 64, 5, 450]
+    plan = B.cf_build_chunks(lens, 256)
+    vals = lambda sid, L: inputs.seq_values(21, sid, lens[sid], 4, 2, 128, "bf16")
+    eng = ChunkAttention(plan, 4, 2, 128, "bf16").load(vals)
+    eng.zero_grads()
+    if K is None:
+        eng.run_forward(); eng.run_backward()
+    else:
+        eng.run_schedule(K)
+    eager = eng.results()
+    ref = P.run_oracle(lens, 4, 2, 128, "bf16", seed=21)
+    P.check(eager, ref, "bf16", "eager")
+    graph = eng.capture_step(K)
+    for replay in range(3):
+        for ch in eng.chunks:                      # eager work between the replays: spoil the outputs
+            ch["o"].fill_(7.0); ch["d_q"].fill_(7.0); ch["lse"].fill_(7.0)
+        eng.grad_arena.fill_(3.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = eng.results()
+        for sid in got:
+            for name in ("o", "lse", "dq"):
+                assert np.array_equal(got[sid][name], eager[sid][name]), (replay, sid, name)
+        P.check(got, ref, "bf16", f"graph replay {replay}")
 
 
 def test_recompute_schedule_gives_same_result():
