@@ -262,8 +262,11 @@ int cf_attn_bwd_batch(const cf_attn_bwd_params *params, int32_t n, void *hip_str
  * Measurement aid (not part of the paper's method): when both events (hipEvent_t, created by the
  * caller with timing enabled) are non-NULL, the NEXT cf_attn_fwd / cf_attn_bwd call on this thread
  * records `start` right before and `stop` right after its main kernel (forward: the attention
- * kernel; backward: the dK/dV kernel, without the dQ kernel that runs before it) on that call's
- * stream, then the hook clears itself.  Passing NULLs clears it.  Never fails.
+ * kernel; backward: the dK/dV kernel -- both of its launches where it takes two -- without the dQ kernel that
+ * runs before it) on that call's
+ * stream, then the hook clears itself.  The batch entry points clear an armed hook without recording (they time
+ * nothing); a call that fails its argument checks leaves it armed.  Passing NULLs clears it.
+ * The hook is per-thread state of the library (its only state besides cf_last_error's message).  Never fails.
  */
 int cf_profile_next_call(void *start_event, void *stop_event);
 

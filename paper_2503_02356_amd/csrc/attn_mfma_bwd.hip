@@ -772,9 +772,9 @@ hipError_t launch_dkv(const cf_attn_bwd_params &b, const BwdWorkspace &ws, const
         // not run concurrently, so they get launches of their own (stream order).
         mfma_dkv_kernel<true><<<dim3((unsigned)g.dkv_blocks), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, 0, nullptr, 0);
         const hipError_t e = hipGetLastError();
-        if (hook.stop) (void)hipEventRecord(hook.stop, s);
         if (e != hipSuccess) return e;
         mfma_dkv_kernel<true><<<dim3((unsigned)g.head_dkv), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, g.head_dkv, nullptr, 0);
+        if (hook.stop) (void)hipEventRecord(hook.stop, s);      // after BOTH launches: together they are the dK/dV pass
     } else {
         mfma_dkv_kernel<false><<<dim3((unsigned)(g.dkv_blocks + g.head_dkv)), 64 * DKV_WAVES, 0, s>>>(b, ws.delta, g.head_dkv, ws.worklist,
                                                                                          (int)ws.worklist_items);

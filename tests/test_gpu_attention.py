@@ -275,3 +275,71 @@ def test_device_entry_point_errors():
     fp.q += 2                                                    # misaligned
     with pytest.raises(B.CfError):
         B.cf_attn_fwd(fp)
+
+
+def test_fused_heads_dkv_accumulates_across_launches():
+    """Section 4.2: earlier chunks rely on the key/value gradients of later chunks.  Three slices of one
+    66 000-token sequence (8 key/value heads) run backward in DESCENDING order into one shared fp32 dK/dV state
+    that starts non-zero.  Every launch has >= 4096 (key tile, kv head) pairs, so all three take the dK/dV
+    kernel's fused-heads mode (plain read-modify-write) and add into the same prefix rows.  The WHOLE state is
+    compared with the oracle's chunked backward applied in the same order, and a second run must reproduce the
+    first bit for bit."""
+    torch.manual_seed(3)
+    dev = "cuda:0"
+    L, T, Hq, Hkv, D = 66000, 200, 16, 8, 128
+    starts = [65400, 65600, 65800]
+    k = torch.randn(L, Hkv, D, device=dev).to(torch.bfloat16)
+    v = torch.randn(L, Hkv, D, device=dev).to(torch.bfloat16)
+    q = torch.randn(L - starts[0], Hq, D, device=dev).to(torch.bfloat16)        # rows of positions >= 65400
+    d_o = torch.randn(L - starts[0], Hq, D, device=dev).to(torch.bfloat16)
+    scale = 1 / np.sqrt(D)
+    init = torch.randn(2, L, Hkv, D, device=dev) * 0.25
+    f = lambda t: t.double().cpu().numpy()
+
+    def run_gpu():
+        dkv = init.clone()
+        outs = []
+        for P_ in reversed(starts):                                              # descending: last slice first
+            a = P_ - starts[0]
+            cu_q = torch.tensor([0, T], dtype=torch.int32, device=dev)
+            cu_k = torch.tensor([0, P_ + T], dtype=torch.int32, device=dev)
+            o = torch.empty(T, Hq, D, device=dev, dtype=torch.bfloat16)
+            lse = torch.empty(Hq, T, device=dev, dtype=torch.float32)
+            fp = B.make_fwd_params(q[a:a + T], k[:P_ + T], v[:P_ + T], o, lse, cu_q, cu_k, scale)
+            assert (fp.n_kv_tokens // 128 + 1) * Hkv >= 4096                     # the fused-heads condition
+            B.cf_attn_fwd(fp)
+            dq = torch.empty(T, Hq, D, device=dev, dtype=torch.bfloat16)
+            ws = torch.empty(B.cf_attn_bwd_workspace_bytes(fp), dtype=torch.uint8, device=dev)
+            B.cf_attn_bwd(B.make_bwd_params(fp, d_o[a:a + T], dq, dkv[0][:P_ + T], dkv[1][:P_ + T], ws))
+            outs.append((P_, o, lse, dq))
+        torch.cuda.synchronize()
+        return dkv, outs
+    dkv, outs = run_gpu()
+    # the oracle, same order, same non-zero start
+    kk, vv = f(k), f(v)
+    rdk, rdv = f(init[0]), f(init[1])
+    max_abs, rel = P.TOL["bf16"]
+    for P_, o, lse, dq in outs:
+        a = P_ - starts[0]
+        cu_q, cu_k = [0, T], [0, P_ + T]
+        ro, rlse = OA.chunk_attn_fwd(f(q[a:a + T]), kk[:P_ + T], vv[:P_ + T], cu_q, cu_k, np.float32(scale))
+        sdk, sdv = np.zeros((P_ + T, Hkv, D)), np.zeros((P_ + T, Hkv, D))
+        rdq = OA.chunk_attn_bwd(f(q[a:a + T]), kk[:P_ + T], vv[:P_ + T], ro, rlse, f(d_o[a:a + T]), cu_q, cu_k,
+                                np.float32(scale), sdk, sdv)
+        rdk[:P_ + T] += sdk
+        rdv[:P_ + T] += sdv
+        got = {0: dict(o=f(o), lse=f(lse), dq=f(dq), dk=np.zeros(1), dv=np.zeros(1))}
+        ref = {0: dict(o=ro, lse=rlse, dq=rdq, dk=np.zeros(1), dv=np.zeros(1))}
+        print(f"slice at {P_}:", P.check(got, ref, "bf16", f"slice at {P_}"), flush=True)
+    # the accumulated part alone (state minus its start), every row of the 66 000, against the oracle's
+    for name, ours, theirs, start in (("dk", dkv[0], rdk, init[0]), ("dv", dkv[1], rdv, init[1])):
+        got_c, ref_c = f(ours) - f(start), theirs - f(start)
+        err = np.abs(got_c - ref_c).max()
+        r2 = np.linalg.norm(got_c - ref_c) / np.linalg.norm(ref_c)
+        # rows below the first slice received all three launches' contributions
+        e3 = np.abs(got_c[:starts[0]] - ref_c[:starts[0]]).max()
+        print(f"state {name}: max-abs {err:.2e} rel-L2 {r2:.2e} (prefix rows, three launches: {e3:.2e})", flush=True)
+        assert err <= max_abs and r2 <= rel, (name, err, r2)
+        assert np.abs(ref_c[:starts[0]]).max() > 0
+    dkv2, _ = run_gpu()
+    assert torch.equal(dkv, dkv2), "fused-heads dK/dV must be bitwise reproducible"
