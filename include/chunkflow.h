@@ -243,6 +243,24 @@ int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p);
 int cf_attn_bwd(const cf_attn_bwd_params *p, void *hip_stream);
 
 /*
+ * cf_attn_bwd for callers that cannot allocate device memory or carry a workspace around: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as cf_attn_bwd,
+ * except that p->workspace / p->workspace_bytes are IGNORED: delta and the dK/dV work list live in a buffer of
+ * CF_STATIC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine) and, like
+ * cf_attn_bwd, only enqueues kernels on the stream.
+ *   - A chunk whose cf_attn_bwd_workspace_bytes exceeds CF_STATIC_SCRATCH_BYTES -> CF_EINVAL (decided on the
+ *     host before any HIP call; n_q_heads * n_tokens * 4 bytes dominate: 64 heads x 32768 tokens need 8.3 MiB).
+ *   - Every call on a GPU uses that GPU's one buffer, which keeps the previous call's contents; nothing in it
+ *     has to start at zero (each call overwrites what it reads).  Calls that OVERLAP on one GPU (two streams,
+ *     two threads) race on it: keep them on one stream or order them with events.
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress); a failure -> CF_EHIP.
+ * Other errors as cf_attn_bwd.
+ */
+#define CF_STATIC_SCRATCH_BYTES (16 << 20)
+int cf_attn_bwd_static(const cf_attn_bwd_params *p, void *hip_stream);
+
+/*
  * Whole-plan launches: several chunks in one call.  The results are those of calling cf_attn_fwd /
  * cf_attn_bwd for params[0], params[1], ... in that order on the stream (dK/dV that several chunks share --
  * the chunks of one long sequence, section 4.2 -- accumulate in exactly that order).  What changes is the

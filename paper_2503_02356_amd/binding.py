@@ -20,7 +20,7 @@ CF_PLAN_MERGE_TAILS = 1
 
 EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_build_chunks_ex", "cf_attn_q_tiles", "cf_plan_free", "cf_plan_get",
            "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_attn_fwd_batch", "cf_attn_bwd_batch",
-           "cf_count_pairs", "cf_profile_next_call"]
+           "cf_count_pairs", "cf_profile_next_call", "cf_attn_bwd_static"]
 
 
 class CfError(RuntimeError):
@@ -91,6 +91,7 @@ def lib():
         L.cf_attn_bwd_workspace_bytes.argtypes = [C.POINTER(AttnFwdParams)]
         L.cf_attn_bwd_workspace_bytes.restype = C.c_int64
         L.cf_attn_bwd.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
+        L.cf_attn_bwd_static.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
         L.cf_attn_fwd_batch.argtypes = [C.POINTER(AttnFwdParams), C.c_int32, C.c_void_p]
         L.cf_attn_bwd_batch.argtypes = [C.POINTER(AttnBwdParams), C.c_int32, C.c_void_p]
         L.cf_schedule_stats.argtypes = [C.c_void_p, C.c_int32, C.POINTER(SchedStats)]
@@ -263,14 +264,19 @@ def cf_attn_bwd_workspace_bytes(params):
     return _check(lib().cf_attn_bwd_workspace_bytes(C.byref(params)))
 
 
+CF_STATIC_SCRATCH_BYTES = 16 << 20
+
+
 def make_bwd_params(fwd_params, d_o, d_q, d_k, d_v, workspace):
+    """workspace: uint8 device tensor, or None for cf_attn_bwd_static (which ignores the field)."""
     b = AttnBwdParams()
     b.f = fwd_params
     b.d_o, b.do_stride_tok, b.do_stride_head = d_o.data_ptr(), d_o.stride(0), d_o.stride(1)
     b.d_q, b.dq_stride_tok, b.dq_stride_head = d_q.data_ptr(), d_q.stride(0), d_q.stride(1)
     assert d_k.stride() == d_v.stride() and d_k.stride(2) == 1
     b.d_k, b.d_v, b.dkv_stride_tok, b.dkv_stride_head = d_k.data_ptr(), d_v.data_ptr(), d_k.stride(0), d_k.stride(1)
-    b.workspace, b.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    if workspace is not None:
+        b.workspace, b.workspace_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
     b._keepalive = (fwd_params, d_o, d_q, d_k, d_v, workspace)      # see make_fwd_params
     return b
 
@@ -296,3 +302,7 @@ def cf_attn_bwd_batch(params_arr, stream=None):
 
 def cf_attn_bwd(params, stream=None):
     _check(lib().cf_attn_bwd(C.byref(params), stream if stream is not None else _stream()))
+
+
+def cf_attn_bwd_static(params, stream=None):
+    _check(lib().cf_attn_bwd_static(C.byref(params), stream if stream is not None else _stream()))

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "common.h"
@@ -113,13 +114,13 @@ extern "C" int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p)
 
 namespace {
 
-// Argument checks of one backward call; on success fills the scratch layout inside the caller's workspace.
-int check_bwd(const cf_attn_bwd_params *b, const char *who, cf::BwdWorkspace *ws)
+// Argument checks of one backward call apart from its scratch memory.
+int check_bwd_tensors(const cf_attn_bwd_params *b, const char *who)
 {
     if (!b) return cf::fail(CF_EINVAL, "%s: params is NULL", who);
     if (int rc = check_fwd(&b->f, who, false)) return rc;
     const cf_attn_fwd_params &p = b->f;
-    if (!b->d_o || !b->d_q || !b->d_k || !b->d_v || !b->workspace)
+    if (!b->d_o || !b->d_q || !b->d_k || !b->d_v)
         return cf::fail(CF_EINVAL, "%s: NULL device pointer", who);
     const int64_t vec = p.dtype == CF_BF16 ? 8 : 4, D = p.head_dim;
     const int64_t strides[] = {b->do_stride_tok, b->do_stride_head, b->dq_stride_tok, b->dq_stride_head};
@@ -129,17 +130,30 @@ int check_bwd(const cf_attn_bwd_params *b, const char *who, cf::BwdWorkspace *ws
                             (long long)s, (long long)vec);
     if (b->dkv_stride_tok < D || b->dkv_stride_head < D || b->dkv_stride_tok % 4 || b->dkv_stride_head % 4)
         return cf::fail(CF_EINVAL, "%s: d_k/d_v strides must be >= head_dim and multiples of 4 elements", who);
-    if (!aligned(b->d_o, 16) || !aligned(b->d_q, 16) || !aligned(b->d_k, 16) || !aligned(b->d_v, 16) ||
-        !aligned(b->workspace, 256))
-        return cf::fail(CF_EINVAL, "%s: d_o, d_q, d_k, d_v must be 16-byte and workspace 256-byte aligned", who);
+    if (!aligned(b->d_o, 16) || !aligned(b->d_q, 16) || !aligned(b->d_k, 16) || !aligned(b->d_v, 16))
+        return cf::fail(CF_EINVAL, "%s: d_o, d_q, d_k, d_v must be 16-byte aligned", who);
+    return CF_OK;
+}
+
+// Lays the backward's scratch (delta, then the dK/dV work list) out in `bytes` bytes of device memory at `base`.
+int carve_workspace(const cf_attn_fwd_params &p, void *base, int64_t bytes, const char *who, const char *what,
+                    cf::BwdWorkspace *ws)
+{
+    if (!base || !aligned(base, 256)) return cf::fail(CF_EINVAL, "%s: %s must be non-NULL and 256-byte aligned", who, what);
     const int64_t need = delta_bytes(p) + worklist_bytes(p);
-    if (b->workspace_bytes < need)
-        return cf::fail(CF_EINVAL, "%s: workspace has %lld bytes, %lld needed", who, (long long)b->workspace_bytes,
-                        (long long)need);
-    ws->delta = static_cast<float *>(b->workspace);
-    ws->worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(b->workspace) + delta_bytes(p)) : nullptr;
+    if (bytes < need)
+        return cf::fail(CF_EINVAL, "%s: %s has %lld bytes, %lld needed", who, what, (long long)bytes, (long long)need);
+    ws->delta = static_cast<float *>(base);
+    ws->worklist = mfma_shape(p) ? reinterpret_cast<int *>(static_cast<char *>(base) + delta_bytes(p)) : nullptr;
     ws->worklist_items = mfma_shape(p) ? cf::dkv_worklist_capacity(p) : 0;
     return CF_OK;
+}
+
+// Argument checks of one backward call; on success fills the scratch layout inside the caller's workspace.
+int check_bwd(const cf_attn_bwd_params *b, const char *who, cf::BwdWorkspace *ws)
+{
+    if (int rc = check_bwd_tensors(b, who)) return rc;
+    return carve_workspace(b->f, b->workspace, b->workspace_bytes, who, "workspace", ws);
 }
 
 int bwd_one(const cf_attn_bwd_params *b, const cf::BwdWorkspace &ws, hipStream_t s, const char *who)
@@ -172,6 +186,52 @@ extern "C" int cf_attn_bwd(const cf_attn_bwd_params *b, void *hip_stream)
     cf::BwdWorkspace ws;
     if (int rc = check_bwd(b, "cf_attn_bwd", &ws)) return rc;
     return bwd_one(b, ws, static_cast<hipStream_t>(hip_stream), "cf_attn_bwd");
+}
+
+// ---- the backward for callers that cannot allocate -------------------------------------------------------------
+// The scratch of cf_attn_bwd_static: one array per GPU, part of the loaded code object, alive until the process
+// ends.  Host code never uses the array's name as an address: the device address is looked up once per device
+// (hipGetSymbolAddress with that device current) and kept in g_static_scratch.
+static __device__ __align__(256) unsigned char scratch[CF_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_static_scratch[kMaxDevices];
+
+// Device address of `scratch` on the current device.
+int static_scratch(const char *who, void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(who, e);
+    if (dev < 0 || dev >= kMaxDevices) return cf::fail(CF_EUNSUPPORTED, "%s: device ordinal %d out of range", who, dev);
+    void *ptr = g_static_scratch[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        // (two threads racing here both get the same address from the runtime)
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(who, e);
+        if (!ptr) return cf::fail(CF_EHIP, "%s: hipGetSymbolAddress returned a NULL address", who);
+        g_static_scratch[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return CF_OK;
+}
+}  // namespace
+
+extern "C" int cf_attn_bwd_static(const cf_attn_bwd_params *b, void *hip_stream)
+{
+    const char *who = "cf_attn_bwd_static";
+    if (int rc = check_bwd_tensors(b, who)) return rc;
+    // the size check comes before any HIP call: an oversized chunk is refused on any host
+    const int64_t need = delta_bytes(b->f) + worklist_bytes(b->f);
+    if (need > (int64_t)CF_STATIC_SCRATCH_BYTES)
+        return cf::fail(CF_EINVAL, "%s: this chunk needs %lld bytes of scratch, the static buffer holds %lld "
+                        "(use cf_attn_bwd with a workspace)", who, (long long)need, (long long)CF_STATIC_SCRATCH_BYTES);
+    void *base = nullptr;
+    if (int rc = static_scratch(who, &base)) return rc;
+    cf::BwdWorkspace ws;
+    if (int rc = carve_workspace(b->f, base, CF_STATIC_SCRATCH_BYTES, who, "static scratch", &ws)) return rc;
+    return bwd_one(b, ws, static_cast<hipStream_t>(hip_stream), who);
 }
 
 extern "C" int cf_attn_fwd_batch(const cf_attn_fwd_params *params, int32_t n, void *hip_stream)

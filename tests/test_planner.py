@@ -234,3 +234,33 @@ def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
         B.cf_build_chunks([3, 4], 4)
     with pytest.raises(RuntimeError, match="missing"):
         B.cf_attn_fwd(B.AttnFwdParams(), None)
+
+
+def test_static_scratch_backward_refuses_oversized_chunks_on_the_host():
+    """cf_attn_bwd_static decides on the host, before any HIP call, that a chunk's scratch (delta =
+    n_q_heads * n_tokens * 4 bytes, plus the work list) does not fit its static buffer: CF_EINVAL on any machine.
+    The pointers are never dereferenced on that path (fake, aligned, non-NULL addresses)."""
+    fp = B.AttnFwdParams()
+    fp.dtype, fp.flags, fp.n_q_heads, fp.n_kv_heads, fp.head_dim = B.CF_BF16, 0, 64, 8, 128
+    fp.softmax_scale = 0.1
+    fp.n_tokens, fp.n_kv_tokens, fp.n_segments = 70000, 70000, 1          # 64 * 70000 * 4 bytes > 16 MiB
+    fake = 1 << 20
+    for name in ("cu_seqlens_q", "cu_seqlens_k", "q", "k", "v", "o", "lse"):
+        setattr(fp, name, fake)
+    for name in ("q_stride_tok", "o_stride_tok"):
+        setattr(fp, name, 64 * 128)
+    fp.kv_stride_tok = 8 * 128
+    fp.q_stride_head = fp.o_stride_head = fp.kv_stride_head = 128
+    bp = B.AttnBwdParams()
+    bp.f = fp
+    bp.d_o = bp.d_q = bp.d_k = bp.d_v = fake
+    bp.do_stride_tok = bp.dq_stride_tok = 64 * 128
+    bp.dkv_stride_tok = 8 * 128
+    bp.do_stride_head = bp.dq_stride_head = bp.dkv_stride_head = 128
+    need = B.cf_attn_bwd_workspace_bytes(fp)
+    assert need > B.CF_STATIC_SCRATCH_BYTES
+    with pytest.raises(B.CfError) as e:
+        B.cf_attn_bwd_static(bp, ctypes.c_void_p(0))
+    assert e.value.code == B.CF_EINVAL and "static buffer" in str(e.value)
+    hdr = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
+    assert re.search(r"#define\s+CF_STATIC_SCRATCH_BYTES\s+\(16\s*<<\s*20\)", hdr)
