@@ -140,6 +140,39 @@ typedef struct {
 } cf_sched_stats;
 int cf_schedule_stats(cf_plan *plan, int32_t K, cf_sched_stats *out);
 
+/*
+ * Pipeline bubble ratio of a 1F1B schedule under the paper's cost model for its pipeline examples (section 3.3:
+ * the time of a micro-batch is proportional to its length, backward = 2 x forward; equation 1: bubble ratio =
+ * total bubble time / total execution time over all stages).  Integer ticks: forward of n tokens = n, backward 2n.
+ *
+ * cf_sim_1f1b_sequences  standard 1F1B (section 3.3) with every sequence a micro-batch of its own, in the given
+ *     order: stage s of p runs p-1-s warm-up forwards, then one forward / one backward alternately, then drains.
+ * cf_sim_1f1b            state-aware 1F1B (section 4.3) over the chunks of a plan: the same shape, but the
+ *     forward-type passes (first forwards and the re-forwards of discarded chunks) and the backward passes are
+ *     those of Algorithm 2 with K kept chunks, each kind in Algorithm 2's order; on every stage a pass waits for the
+ *     previous op of its own dependency group; a stage starts a forward that keeps activations while it holds fewer
+ *     than p-s kept chunks or while the next backward may not run yet, otherwise it runs the next backward.
+ *     Groups are taken standalone chunks first, then the dependent groups (the numbering of the paper's chunk
+ *     figure); CF_SIM_PLAN_ORDER takes them in plan order instead.
+ * Every op starts as early as its stage and its pipeline neighbour allow (forward: the same op one stage earlier;
+ * backward: one stage later).
+ *   out->makespan        ticks until the last stage is done
+ *   out->busy_per_stage  ticks of work on each stage (equal on all stages; re-forwards count as work)
+ *   out->bubble_ticks / out->total_ticks = the bubble ratio, total_ticks = n_stages * makespan
+ * Reproduces the paper's 57.14 %, 42.8 % (3/7), 47.8 % (22/46) and 60 %; its 54.1 % (ChunkSize 2 Units, K = 1) is
+ * not reachable in this cost model (every pass there lasts an even number of Units).
+ * Errors: NULL arguments, K < 1, n_stages < 1, a length < 1, unknown flags -> CF_EINVAL.  The plan's stored schedule
+ * (cf_build_schedule) is not touched.
+ */
+typedef struct {
+    int64_t makespan, busy_per_stage, bubble_ticks, total_ticks;
+    int64_t n_ops;
+    int32_t n_stages, reserved;
+} cf_pipeline_stats;
+enum { CF_SIM_PLAN_ORDER = 1 };
+int cf_sim_1f1b_sequences(const int64_t *seq_lens, int64_t n_seqs, int32_t n_stages, cf_pipeline_stats *out);
+int cf_sim_1f1b(cf_plan *plan, int32_t K, int32_t n_stages, uint32_t flags, cf_pipeline_stats *out);
+
 /* ============================================================================================
  * Device kernels.
  * ========================================================================================== */

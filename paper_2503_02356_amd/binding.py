@@ -20,7 +20,7 @@ CF_PLAN_MERGE_TAILS = 1
 
 EXPORTS = ["cf_last_error", "cf_version", "cf_build_chunks", "cf_build_chunks_ex", "cf_attn_q_tiles", "cf_plan_free", "cf_plan_get",
            "cf_build_schedule", "cf_schedule_stats", "cf_attn_fwd", "cf_attn_bwd_workspace_bytes", "cf_attn_bwd", "cf_attn_fwd_batch", "cf_attn_bwd_batch",
-           "cf_count_pairs", "cf_profile_next_call", "cf_attn_bwd_static"]
+           "cf_count_pairs", "cf_profile_next_call", "cf_attn_bwd_static", "cf_sim_1f1b", "cf_sim_1f1b_sequences"]
 
 
 class CfError(RuntimeError):
@@ -47,6 +47,11 @@ class SchedOp(C.Structure):
 class SchedStats(C.Structure):
     _fields_ = [("n_forward", C.c_int64), ("n_backward", C.c_int64), ("n_reforward", C.c_int64),
                 ("peak_kept_chunks", C.c_int64), ("peak_kept_tokens", C.c_int64), ("state_tokens", C.c_int64)]
+
+
+class PipelineStats(C.Structure):
+    _fields_ = [("makespan", C.c_int64), ("busy_per_stage", C.c_int64), ("bubble_ticks", C.c_int64),
+                ("total_ticks", C.c_int64), ("n_ops", C.c_int64), ("n_stages", C.c_int32), ("reserved", C.c_int32)]
 
 
 class AttnFwdParams(C.Structure):
@@ -91,6 +96,8 @@ def lib():
         L.cf_attn_bwd_workspace_bytes.argtypes = [C.POINTER(AttnFwdParams)]
         L.cf_attn_bwd_workspace_bytes.restype = C.c_int64
         L.cf_attn_bwd.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
+        L.cf_sim_1f1b.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_uint32, C.POINTER(PipelineStats)]
+        L.cf_sim_1f1b_sequences.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.POINTER(PipelineStats)]
         L.cf_attn_bwd_static.argtypes = [C.POINTER(AttnBwdParams), C.c_void_p]
         L.cf_attn_fwd_batch.argtypes = [C.POINTER(AttnFwdParams), C.c_int32, C.c_void_p]
         L.cf_attn_bwd_batch.argtypes = [C.POINTER(AttnBwdParams), C.c_int32, C.c_void_p]
@@ -162,6 +169,12 @@ class Plan:
         _check(lib().cf_schedule_stats(self._h, int(K), C.byref(st)))
         return {name: int(getattr(st, name)) for name, _ in SchedStats._fields_}
 
+    def sim_1f1b(self, K, n_stages, flags=0):
+        """cf_sim_1f1b as a dict."""
+        st = PipelineStats()
+        _check(lib().cf_sim_1f1b(self._h, int(K), int(n_stages), int(flags), C.byref(st)))
+        return {name: int(getattr(st, name)) for name, _ in PipelineStats._fields_ if name != "reserved"}
+
     def close(self):
         if self._h:
             lib().cf_plan_free(self._h)
@@ -186,6 +199,16 @@ def cf_build_chunks_ex(seq_lens, chunk_size, flags):
     h = C.c_void_p()
     _check(lib().cf_build_chunks_ex(lens.ctypes.data_as(C.c_void_p), len(lens), int(chunk_size), int(flags), C.byref(h)))
     return Plan(h)
+
+
+CF_SIM_PLAN_ORDER = 1
+
+
+def cf_sim_1f1b_sequences(seq_lens, n_stages):
+    lens = np.ascontiguousarray(seq_lens, dtype=np.int64)
+    st = PipelineStats()
+    _check(lib().cf_sim_1f1b_sequences(lens.ctypes.data_as(C.c_void_p), len(lens), int(n_stages), C.byref(st)))
+    return {name: int(getattr(st, name)) for name, _ in PipelineStats._fields_ if name != "reserved"}
 
 
 def cf_count_pairs(cu_q, cu_k):

@@ -308,6 +308,178 @@ extern "C" int cf_schedule_stats(cf_plan *p, int32_t K, cf_sched_stats *out)
     return CF_OK;
 }
 
+// ---- pipeline bubble simulator (sections 3.3, 4.3, 5) ---------------------------------------------------------
+namespace {
+
+struct SimOp {
+    bool backward;
+    int64_t ticks;
+    int32_t group;      // dependency group of the op's chunk (plain 1F1B: one group per micro-batch)
+    bool keeps;         // a forward whose activations stay until the chunk's backward
+};
+
+// Order in which one stage runs the ops: forward-type ops in list order, backward ops in list order, a forward
+// that keeps activations while fewer than `limit` chunks are held or while the next backward may not run yet,
+// otherwise the next backward.  An op may run once the previous op of its group (prev[i], or -1) has run here.
+bool stage_order(const std::vector<SimOp> &ops, const std::vector<int64_t> &prev, int64_t limit, std::vector<int64_t> &order)
+{
+    const int64_t n = (int64_t)ops.size();
+    std::vector<char> ran((size_t)n, 0);
+    order.clear();
+    int64_t f = 0, b = 0, held = 0;
+    auto next_of = [&](int64_t from, bool backward) {
+        while (from < n && ops[(size_t)from].backward != backward) ++from;
+        return from;
+    };
+    f = next_of(0, false);
+    b = next_of(0, true);
+    auto allowed = [&](int64_t i) { return i < n && (prev[(size_t)i] < 0 || ran[(size_t)prev[(size_t)i]]); };
+    while (f < n || b < n) {
+        const bool f_ok = allowed(f), b_ok = allowed(b);
+        int64_t take;
+        if (f_ok && (!ops[(size_t)f].keeps || held < limit || !b_ok)) {
+            take = f;
+            held += ops[(size_t)f].keeps;
+            f = next_of(f + 1, false);
+        } else if (b_ok) {
+            take = b;
+            --held;
+            b = next_of(b + 1, true);
+        } else {
+            return false;
+        }
+        ran[(size_t)take] = 1;
+        order.push_back(take);
+    }
+    return true;
+}
+
+// Earliest-start timeline of the per-stage orders: a forward-type op waits for the same op one stage up the
+// pipeline, a backward op for the same op one stage down.  A stage is re-examined when a neighbour finishes an
+// op (a queue of stages to look at; no repeated sweeps).
+int simulate_pipeline(const std::vector<SimOp> &ops, int32_t n_stages, const char *who, cf_pipeline_stats *out)
+{
+    const int64_t n = (int64_t)ops.size();
+    const int32_t p = n_stages;
+    std::vector<int64_t> prev((size_t)n, -1);
+    {
+        std::vector<int64_t> last;
+        for (int64_t i = 0; i < n; ++i) {
+            const size_t g = (size_t)ops[(size_t)i].group;
+            if (last.size() <= g) last.resize(g + 1, -1);
+            prev[(size_t)i] = last[g];
+            last[g] = i;
+        }
+    }
+    std::vector<std::vector<int64_t>> order((size_t)p);
+    for (int32_t s = 0; s < p; ++s)
+        if (!stage_order(ops, prev, p - s, order[(size_t)s]))
+            return cf::fail(CF_EINVAL, "%s: the schedule cannot be followed on stage %d", who, s);
+    std::vector<std::vector<int64_t>> end((size_t)p, std::vector<int64_t>((size_t)n, -1));
+    std::vector<int64_t> cursor((size_t)p, 0), free_at((size_t)p, 0);
+    std::vector<int32_t> todo;
+    std::vector<char> queued((size_t)p, 1);
+    for (int32_t s = p - 1; s >= 0; --s) todo.push_back(s);     // popped from the back: stage 0 first
+    int64_t done = 0, busy = 0;
+    while (!todo.empty()) {
+        const int32_t s = todo.back();
+        todo.pop_back();
+        queued[(size_t)s] = 0;
+        bool progressed = false;
+        while (cursor[(size_t)s] < n) {
+            const int64_t i = order[(size_t)s][(size_t)cursor[(size_t)s]];
+            const SimOp &op = ops[(size_t)i];
+            const int32_t from = op.backward ? s + 1 : s - 1;
+            int64_t ready = 0;
+            if (from >= 0 && from < p) {
+                ready = end[(size_t)from][(size_t)i];
+                if (ready < 0) break;
+            }
+            const int64_t start = ready > free_at[(size_t)s] ? ready : free_at[(size_t)s];
+            free_at[(size_t)s] = end[(size_t)s][(size_t)i] = start + op.ticks;
+            if (s == 0) busy += op.ticks;
+            ++cursor[(size_t)s];
+            ++done;
+            progressed = true;
+        }
+        if (progressed)
+            for (int32_t nb : {s - 1, s + 1})
+                if (nb >= 0 && nb < p && !queued[(size_t)nb] && cursor[(size_t)nb] < n) {
+                    queued[(size_t)nb] = 1;
+                    todo.push_back(nb);
+                }
+    }
+    if (done != n * p) return cf::fail(CF_EINVAL, "%s: the stage orders deadlock", who);
+    cf_pipeline_stats st = {};
+    st.n_stages = p;
+    st.n_ops = n;
+    st.busy_per_stage = busy;
+    for (int32_t s = 0; s < p; ++s)
+        if (free_at[(size_t)s] > st.makespan) st.makespan = free_at[(size_t)s];
+    st.total_ticks = (int64_t)p * st.makespan;
+    st.bubble_ticks = st.total_ticks - (int64_t)p * busy;
+    *out = st;
+    return CF_OK;
+}
+
+}  // namespace
+
+extern "C" int cf_sim_1f1b_sequences(const int64_t *seq_lens, int64_t n_seqs, int32_t n_stages, cf_pipeline_stats *out)
+{
+    const char *who = "cf_sim_1f1b_sequences";
+    if (!out || n_seqs < 0 || (n_seqs > 0 && !seq_lens)) return cf::fail(CF_EINVAL, "%s: bad argument", who);
+    if (n_stages < 1) return cf::fail(CF_EINVAL, "%s: n_stages = %d < 1", who, n_stages);
+    try {
+        // every micro-batch is a group of its own: forward (kept), then backward -- Algorithm 2 with N = 1
+        std::vector<SimOp> ops;
+        for (int64_t i = 0; i < n_seqs; ++i) {
+            if (seq_lens[i] < 1 || seq_lens[i] > (INT64_MAX >> 24)) return cf::fail(CF_EINVAL, "%s: seq_lens[%lld] out of range", who, (long long)i);
+            ops.push_back({false, seq_lens[i], (int32_t)i, true});
+            ops.push_back({true, 2 * seq_lens[i], (int32_t)i, false});
+        }
+        return simulate_pipeline(ops, n_stages, who, out);
+    } catch (const std::bad_alloc &) {
+        return cf::fail(CF_ENOMEM, "%s: out of host memory", who);
+    }
+}
+
+extern "C" int cf_sim_1f1b(cf_plan *p, int32_t K, int32_t n_stages, uint32_t flags, cf_pipeline_stats *out)
+{
+    const char *who = "cf_sim_1f1b";
+    if (!p || !out) return cf::fail(CF_EINVAL, "%s: NULL argument", who);
+    if (K < 1 || n_stages < 1) return cf::fail(CF_EINVAL, "%s: K = %d, n_stages = %d must be >= 1", who, K, n_stages);
+    if (flags & ~(uint32_t)CF_SIM_PLAN_ORDER) return cf::fail(CF_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    try {
+        const int64_t n_groups = (int64_t)p->group_seq_id.size();
+        std::vector<int64_t> group_order;
+        if (flags & CF_SIM_PLAN_ORDER) {
+            for (int64_t g = 0; g < n_groups; ++g) group_order.push_back(g);
+        } else {                                   // standalone chunks first, then the dependent groups
+            for (int pass = 0; pass < 2; ++pass)
+                for (int64_t g = 0; g < n_groups; ++g)
+                    if ((p->group_seq_id[g] >= 0) == (pass == 1)) group_order.push_back(g);
+        }
+        std::vector<SimOp> ops;
+        for (size_t n = 0; n < group_order.size(); ++n) {
+            const int64_t g = group_order[n];
+            const int64_t *c = p->group_chunks.data() + p->group_chunk_ptr[g];
+            const int64_t N = p->group_chunk_ptr[g + 1] - p->group_chunk_ptr[g];
+            const int64_t kept_from = N > K ? N - K : 0;
+            auto fwd = [&](int64_t m, bool keep) { ops.push_back({false, (int64_t)p->chunk_tokens[c[m]], (int32_t)n, keep}); };
+            auto bwd = [&](int64_t m) { ops.push_back({true, 2 * (int64_t)p->chunk_tokens[c[m]], (int32_t)n, false}); };
+            for (int64_t m = 0; m < N; ++m) fwd(m, m >= kept_from);
+            for (int64_t m = N - 1; m >= kept_from; --m) bwd(m);
+            for (int64_t m = kept_from - 1; m >= 0; --m) {
+                fwd(m, true);
+                bwd(m);
+            }
+        }
+        return simulate_pipeline(ops, n_stages, who, out);
+    } catch (const std::bad_alloc &) {
+        return cf::fail(CF_ENOMEM, "%s: out of host memory", who);
+    }
+}
+
 extern "C" int64_t cf_count_pairs(const int32_t *cu_q, const int32_t *cu_k, int32_t n_segments)
 {
     if (!cu_q || !cu_k || n_segments < 0) return cf::fail(CF_EINVAL, "cf_count_pairs: bad argument");

@@ -36,7 +36,7 @@ def assert_same_plan(lens, C, merge_tails=False):
 
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
-    declared = set(re.findall(r"\b(cf_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(cf_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     so = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
@@ -264,3 +264,47 @@ def test_static_scratch_backward_refuses_oversized_chunks_on_the_host():
     assert e.value.code == B.CF_EINVAL and "static buffer" in str(e.value)
     hdr = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
     assert re.search(r"#define\s+CF_STATIC_SCRATCH_BYTES\s+\(16\s*<<\s*20\)", hdr)
+
+
+def test_pipeline_simulator_bit_exact_against_the_oracle():
+    """cf_sim_1f1b / cf_sim_1f1b_sequences (sections 3.3, 4.3, 5) against oracle/pipeline.py in integer ticks:
+    the paper's example and random batches, every K and stage count, both group orders."""
+    from fractions import Fraction
+    from oracle import pipeline as PL
+    r = B.cf_sim_1f1b_sequences([4, 2, 1, 1], 4)
+    assert (r["makespan"], r["busy_per_stage"]) == (56, 24) and Fraction(r["bubble_ticks"], r["total_ticks"]) == Fraction(4, 7)
+    plan = B.cf_build_chunks([4, 2, 1, 1], 2)
+    assert plan.sim_1f1b(2, 4)["makespan"] == 46 and plan.sim_1f1b(1, 4)["makespan"] == 62
+    plan = B.cf_build_chunks([4, 2, 1, 1], 4)
+    r = plan.sim_1f1b(1, 4)
+    assert Fraction(r["bubble_ticks"], r["total_ticks"]) == Fraction(3, 5)
+    rng = np.random.default_rng(17)
+    for trial in range(400):
+        n = int(rng.integers(1, 14))
+        C = int(rng.integers(1, 40))
+        lens = [int(x) for x in rng.integers(1, 4 * C + 2, size=n)]
+        K, p = int(rng.integers(1, 5)), int(rng.integers(1, 7))
+        merge = bool(trial % 5 == 0)
+        chunks, groups = CK.build_chunks(lens, C, merge_tails=merge)
+        plan = B.cf_build_chunks_ex(lens, C, B.CF_PLAN_MERGE_TAILS if merge else 0)
+        for flags, first in ((0, True), (B.CF_SIM_PLAN_ORDER, False)):
+            ref = PL.state_aware_1f1b(chunks, groups, K, p, standalone_first=first)
+            got = plan.sim_1f1b(K, p, flags)
+            assert got["makespan"] == ref["makespan"] and got["busy_per_stage"] == ref["busy"][0], (lens, C, K, p, flags)
+            assert got["n_ops"] == len(ref["ops"]) and got["total_ticks"] == p * ref["makespan"]
+            assert Fraction(got["bubble_ticks"], got["total_ticks"]) == ref["bubble_ratio"]
+        ref = PL.one_f_one_b(lens, p)
+        got = B.cf_sim_1f1b_sequences(lens, p)
+        assert got["makespan"] == ref["makespan"] and got["busy_per_stage"] == ref["busy"][0]
+        plan.close()
+
+
+def test_pipeline_simulator_errors():
+    plan = B.cf_build_chunks([5, 3], 4)
+    for K, p, flags in ((0, 4, 0), (1, 0, 0), (1, 4, 8)):
+        with pytest.raises(B.CfError) as e:
+            plan.sim_1f1b(K, p, flags)
+        assert e.value.code == B.CF_EINVAL
+    with pytest.raises(B.CfError):
+        B.cf_sim_1f1b_sequences([3, 0], 2)
+    assert B.cf_sim_1f1b_sequences([], 3)["makespan"] == 0
