@@ -25,6 +25,8 @@ WORKLOADS = {                       # name -> inputs.CONFIGS key
 # what the same counters read for the 512 MiB copy kernel below.  A measured constant of the build the profile was
 # taken on, not something this run re-measures.
 MEASURED_TRAFFIC_BYTES = {"config2_packed_8k": 597e6, "config3_long32k_mixed": 1150e6, "config5_long256k_32k": None}
+TRAFFIC_SOURCE = {"config2_packed_8k": "profiles/bench_config2_packed_8k_kernels.txt",
+                  "config3_long32k_mixed": "profiles/bench_config3_long32k_mixed_kernels.txt", "config5_long256k_32k": None}
 
 
 def cpu_baseline(lens, cfg, seed, budget_pairs):
@@ -54,31 +56,9 @@ def cpu_baseline(lens, cfg, seed, budget_pairs):
             "sample": f"first {n_seq} short sequences of the batch, {pairs} unmasked pairs, fwd+bwd fp64, {secs:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--streams", type=int, default=1, help="HIP streams the dependency groups are dealt over")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-tile-tables", action="store_true", help="let the kernels search cu_seqlens instead of reading "
-                    "the host-built tile tables (cf_attn_q_tiles)")
-    ap.add_argument("--cpu-pairs", type=float, default=3e7, help="unmasked pairs in the oracle's timed sample")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
-
-    import numpy as np
-    import torch
-    from paper_2503_02356_amd import binding as B
-    from paper_2503_02356_amd import inputs
-    from paper_2503_02356_amd.runner import ChunkAttention
-
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    cfg_key = WORKLOADS[args.workload]
+def measure(workload, args, torch, np, B, inputs, ChunkAttention, extras=True):
+    """Builds the workload's plan and tensors on the GPU, times args.steps steps, and returns the result block."""
+    cfg_key = WORKLOADS[workload]
     cfg = inputs.CONFIGS[cfg_key]
     Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
 
@@ -95,7 +75,7 @@ def main():
         vals = lambda sid, L: inputs.seq_values_device(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"], "cuda:0")
     else:
         vals = lambda sid, L: inputs.seq_values(args.seed, sid, int(lens[sid]), Hq, Hkv, D, cfg["dtype"])
-    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams, fused_launch=True,
+    eng = ChunkAttention(plan, Hq, Hkv, D, cfg["dtype"], n_streams=args.streams, fused_launch=extras,
                          tile_tables=not args.no_tile_tables).load(vals)
     pairs = eng.total_pairs
     flop_step = 14.0 * D * Hq * pairs
@@ -106,14 +86,6 @@ def main():
         eng.zero_grads()
         eng.run_forward(fused=fused)
         eng.run_backward(fused=fused)
-
-    # A plain streaming kernel of known size (reads 512 MiB, writes 512 MiB; larger than the 256 MiB
-    # memory-side cache): the yardstick the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the attention
-    # kernels are scaled by.  bitwise_not so that it shows up under a kernel name of its own.
-    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-    cal_dst = torch.empty_like(cal_src)
-    torch.bitwise_not(cal_src, out=cal_dst)
-    del cal_src, cal_dst
 
     for _ in range(args.warmup):
         step()
@@ -138,14 +110,15 @@ def main():
         eng.zero_grads()
         eng.run_backward()
     part_reps = max(1, min(args.steps, 5))
-    step(fused=True)                                   # warm-up of the whole-plan launch
-    fused_ms = wall_ms(lambda: step(fused=True), part_reps)
-    graph_ms = None
-    if args.streams == 1:                              # the same step recorded once into a HIP graph and replayed
-        graph = eng.capture_step()
-        graph.replay()
-        graph_ms = wall_ms(graph.replay, part_reps)
-        del graph
+    fused_ms = graph_ms = None
+    if extras:
+        step(fused=True)                                   # warm-up of the whole-plan launch
+        fused_ms = wall_ms(lambda: step(fused=True), part_reps)
+        if args.streams == 1:                              # the same step recorded once into a HIP graph and replayed
+            graph = eng.capture_step()
+            graph.replay()
+            graph_ms = wall_ms(graph.replay, part_reps)
+            del graph
     fwd_pass_ms = wall_ms(eng.run_forward, part_reps)
     bwd_pass_ms = wall_ms(bwd_pass, part_reps)
 
@@ -172,29 +145,84 @@ def main():
     bwd_avg_ms = float(np.mean(bwd_ms))
     fwd_avg_ms = float(np.mean(fwd_ms))
     achieved = bwd_flop_per_launch / (bwd_avg_ms * 1e-3) / 1e12
+    # Algorithmic HBM bytes of an average dK/dV launch: Q and dO read once, K and V once, LSE and delta, and the
+    # fp32 dK/dV rows read and written once.
+    algo_bytes = float(np.mean([2 * ch["T"] * Hq * D * 2 + 2 * ch["k"].shape[0] * Hkv * D * 2 + 8 * ch["T"] * Hq
+                                + 2 * 2 * ch["k"].shape[0] * Hkv * D * 4 for ch in eng.chunks]))
     roofline = {"bound": "mfma", "kernel": "mfma_dkv_kernel", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES[args.workload],
+                "traffic": MEASURED_TRAFFIC_BYTES[workload], "traffic_source": TRAFFIC_SOURCE[workload],
+                "algorithmic_bytes": algo_bytes,
                 "avg_launch_ms": bwd_avg_ms, "launches_per_step": n_chunks,
                 "fwd_kernel": {"kernel": "mfma_fwd_kernel", "avg_launch_ms": fwd_avg_ms,
                                "achieved": 4.0 * D * Hq * pairs / n_chunks / (fwd_avg_ms * 1e-3) / 1e12}}
-
-    out = {"metric": "chunk attention fwd+bwd TFLOP/s (unmasked pairs)", "value": tflops, "unit": "TFLOP/s",
-           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": args.workload, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "chunk_size": C,
+    out = {"value": tflops, "unit": "TFLOP/s", "ms_per_step": ms_per_step, "steps": args.steps, "warmup": args.warmup,
+           "config": {"workload": workload, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "chunk_size": C,
                       "n_sequences": int(len(lens)), "n_chunks": n_chunks, "tokens": int(plan.total_tokens),
                       "unmasked_pairs": int(pairs), "flop_per_step": flop_step, "seed": args.seed,
                       "tile_tables": not args.no_tile_tables, "plan_build_ms": plan_ms, "streams": args.streams},
-           "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops_used": PEAK_BF16_TFLOPS,
-           "whole_plan_launch": {"ms_per_step": fused_ms, "tflops": flop_step / (fused_ms * 1e-3) / 1e12,
-                                 "what": "same step through cf_attn_fwd_batch / cf_attn_bwd_batch"},
-           "graph_replay": None if graph_ms is None else {"ms_per_step": graph_ms, "tflops": flop_step / (graph_ms * 1e-3) / 1e12,
-                                                           "what": "the per-chunk step captured in a HIP graph, one replay per step"},
+           "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
            "fwd_only": {"ms": fwd_pass_ms, "tflops": 4.0 * D * Hq * pairs / (fwd_pass_ms * 1e-3) / 1e12},
            "bwd_only": {"ms": bwd_pass_ms, "tflops": 10.0 * D * Hq * pairs / (bwd_pass_ms * 1e-3) / 1e12,
                         "includes": "zeroing of the dK/dV buffers"},
            "roofline": roofline}
+    if fused_ms is not None:
+        out["whole_plan_launch"] = {"ms_per_step": fused_ms, "tflops": flop_step / (fused_ms * 1e-3) / 1e12,
+                                    "what": "same step through cf_attn_fwd_batch / cf_attn_bwd_batch"}
+    if graph_ms is not None:
+        out["graph_replay"] = {"ms_per_step": graph_ms, "tflops": flop_step / (graph_ms * 1e-3) / 1e12,
+                               "what": "the per-chunk step captured in a HIP graph, one replay per step"}
+    return out, lens, cfg
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--streams", type=int, default=1, help="HIP streams the dependency groups are dealt over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tile-tables", action="store_true", help="let the kernels search cu_seqlens instead of reading "
+                    "the host-built tile tables (cf_attn_q_tiles)")
+    ap.add_argument("--cpu-pairs", type=float, default=3e7, help="unmasked pairs in the oracle's timed sample")
+    ap.add_argument("--no-second-config", action="store_true", help="skip the config-3 block that the default run "
+                    "(headline = config 2) adds to the same line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2503_02356_amd import binding as B
+    from paper_2503_02356_amd import inputs
+    from paper_2503_02356_amd.runner import ChunkAttention
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    # A plain streaming kernel of known size (reads 512 MiB, writes 512 MiB; larger than the 256 MiB
+    # memory-side cache): the yardstick the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the attention
+    # kernels are scaled by.  bitwise_not so that it shows up under a kernel name of its own.
+    cal_src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    torch.bitwise_not(cal_src, out=cal_dst)
+    del cal_src, cal_dst
+
+    res, lens, cfg = measure(args.workload, args, torch, np, B, inputs, ChunkAttention)
+    out = {"metric": "chunk attention fwd+bwd TFLOP/s (unmasked pairs)", "value": res["value"], "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "peak_tflops_used": PEAK_BF16_TFLOPS}
+    out.update({k: v for k, v in res.items() if k not in ("value", "unit", "ms_per_step", "steps", "warmup")})
+    # The spec names both chunk-8192 GQA configs: the default run times config 3 too (its own plan, tensors,
+    # warm-up and timed steps, after config 2's have been freed) and reports it in the same line.
+    second = "config3_long32k_mixed"
+    if args.workload == "config2_packed_8k" and not args.no_second_config:
+        torch.cuda.empty_cache()
+        res3, _, _ = measure(second, args, torch, np, B, inputs, ChunkAttention, extras=False)
+        out[second] = res3
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(lens, cfg, args.seed, args.cpu_pairs)
     print(json.dumps(out), flush=True)

@@ -179,8 +179,13 @@ int cf_sim_1f1b(cf_plan *plan, int32_t K, int32_t n_stages, uint32_t flags, cf_p
 
 enum { CF_BF16 = 0, CF_FP32 = 1 };
 /* flags: CF_FLAG_SCALAR_KERNELS runs the plain scalar kernels even where an MFMA kernel exists
- * (same results up to rounding; for cross-checks). */
-enum { CF_FLAG_SCALAR_KERNELS = 1 };
+ * (same results up to rounding; for cross-checks).
+ * CF_FLAG_DKV_SINGLE_WRITER (backward, bf16 head_dim 128): every dK/dV row is updated by ONE workgroup that loops
+ * over the query heads of its key/value head, with a plain read-modify-write -- dK/dV are then bitwise reproducible
+ * from run to run.  Without the flag the library takes that mode only when a launch has enough key tiles to fill
+ * the GPU that way (>= 4096 key-tile x kv-head pairs: long prefixes) and otherwise splits the query heads of a
+ * group over workgroups that meet in dK/dV through fp32 atomic adds (faster on short chunks; last bits vary). */
+enum { CF_FLAG_SCALAR_KERNELS = 1, CF_FLAG_DKV_SINGLE_WRITER = 2 };
 
 /*
  * One chunk of attention (sections 2.1, 2.2, 4.2).  The chunk has n_segments segments; segment g

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libchunkflow.so")
 CF_OK, CF_EINVAL, CF_EUNSUPPORTED, CF_ENOMEM, CF_EHIP = 0, -1, -2, -3, -4
 CF_BF16, CF_FP32 = 0, 1
 CF_FLAG_SCALAR_KERNELS = 1
+CF_FLAG_DKV_SINGLE_WRITER = 2
 CF_OP_FWD_KEEP, CF_OP_FWD_DISCARD, CF_OP_BWD = 0, 1, 2
 
 CF_PLAN_MERGE_TAILS = 1

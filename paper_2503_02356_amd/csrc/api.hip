@@ -10,6 +10,8 @@
 
 namespace {
 
+constexpr int kKnownFlags = CF_FLAG_SCALAR_KERNELS | CF_FLAG_DKV_SINGLE_WRITER;
+
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 int check_fwd(const cf_attn_fwd_params *p, const char *who, bool sizes_only)
@@ -30,7 +32,7 @@ int check_fwd(const cf_attn_fwd_params *p, const char *who, bool sizes_only)
         return cf::fail(CF_EINVAL, "%s: n_segments %d > n_tokens %d (empty segments are not allowed)", who,
                         p->n_segments, p->n_tokens);
     if (sizes_only) return CF_OK;
-    if (p->flags & ~CF_FLAG_SCALAR_KERNELS) return cf::fail(CF_EINVAL, "%s: unknown flags 0x%x", who, p->flags);
+    if (p->flags & ~kKnownFlags) return cf::fail(CF_EINVAL, "%s: unknown flags 0x%x", who, p->flags);
     if (!p->cu_seqlens_q || !p->cu_seqlens_k || !p->q || !p->k || !p->v || !p->o || !p->lse)
         return cf::fail(CF_EINVAL, "%s: NULL device pointer", who);
     if (!(p->softmax_scale == p->softmax_scale))
@@ -107,7 +109,7 @@ extern "C" int cf_attn_fwd(const cf_attn_fwd_params *p, void *hip_stream)
 extern "C" int64_t cf_attn_bwd_workspace_bytes(const cf_attn_fwd_params *p)
 {
     if (int rc = check_fwd(p, "cf_attn_bwd_workspace_bytes", true)) return rc;
-    if (p->flags & ~CF_FLAG_SCALAR_KERNELS)
+    if (p->flags & ~kKnownFlags)
         return cf::fail(CF_EINVAL, "cf_attn_bwd_workspace_bytes: unknown flags 0x%x", p->flags);
     return delta_bytes(*p) + worklist_bytes(*p);
 }

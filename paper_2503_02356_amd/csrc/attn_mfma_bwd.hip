@@ -288,6 +288,22 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         // P: register i is query row q0 + 32*mb + (i/4)*8 + 4*half + i%4, column = this lane's key.  The causal
         // mask is a select on every block (no branch around arithmetic that feeds the MFMAs).
         const int lim = kv_idx - off - q0 - mb * 32 - half * 4;   // masked iff lim > 8*g4 + j
+        // only a block that crosses the diagonal (its last key lies after its first query) needs the selects
+        const bool crosses = kt0 + 32 * pw + 31 - off - q0 - mb * 32 > 0;     // wave-uniform
+        if (!crosses) {
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4 l4 = *(const f32x4 *)(lse_s + mb * 32 + g4 * 8 + half * 4);
+                f32x4 pw4;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[g4 * 4 + j], c2, -l4[j]));
+                    s[g4 * 4 + j] = pv;
+                    pw4[j] = pv;
+                }
+                *(f32x4 *)(slot + g4 * 1024) = pw4;
+            }
+        } else
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
             const f32x4 l4 = *(const f32x4 *)(lse_s + mb * 32 + g4 * 8 + half * 4);
@@ -644,6 +660,14 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
                             }
                         __builtin_amdgcn_sched_barrier(0);
                     }
+                    if (!need_mask) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
+                            if (DELTA_PASS) dsum += pv * dp[i];
+                            else dp[i] = pv * (dp[i] - dlt);
+                        }
+                    } else
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], c2, -lse2));
@@ -748,7 +772,7 @@ BwdShape bwd_shape(const cf_attn_fwd_params &p, const BwdWorkspace &ws)
     const int64_t kv_tiles = (int64_t)p.n_kv_tokens / BKV + p.n_segments;
     const int64_t q_tiles = p.q_tiles ? (int64_t)p.n_q_tiles : (int64_t)p.n_tokens / BM + p.n_segments;
     // Fusing the heads of a group into one workgroup needs enough key tiles to fill 256 CUs several times.
-    g.fused = kv_tiles * p.n_kv_heads >= 4096;
+    g.fused = kv_tiles * p.n_kv_heads >= 4096 || (p.flags & CF_FLAG_DKV_SINGLE_WRITER);
     g.dq_blocks = q_tiles * p.n_q_heads;
     g.head_dq = p.n_segments * p.n_q_heads;
     g.head_dkv = p.n_segments * p.n_kv_heads;

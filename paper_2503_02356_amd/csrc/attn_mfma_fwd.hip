@@ -23,6 +23,7 @@ constexpr int BN = 64;         // key rows per tile
 constexpr int D = 128;
 constexpr int TILE_BYTES = BN * 256;          // one swizzled K or V tile (see mfma_common.h)
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // K then V
+constexpr float kLazy = 8.f;                  // log2 units a row maximum may exceed the running reference before O is rescaled
 
 // id: index of the workgroup among those of this chunk
 __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, char *stage_a, char *stage_b)
@@ -135,24 +136,30 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[1][i]);
             mx = max_with_other_half(mx);
-            const float m_new = fmaxf(m_run, mx * c2);
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // first tile: exp2(-inf) = 0
-            m_run = m_new;
-            float rs = 0.f;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    s[mb][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][i], c2, -m_new));
-                    rs += s[mb][i];
-                }
-            l_run = l_run * alpha + rs;
-            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+            // Lazy rescale: the running reference m_run only moves when a row's new maximum exceeds it by more than
+            // 2^kLazy; until then P = exp2(s - m_run) <= 2^kLazy, exact enough in the fp32 sums and in bf16 alike,
+            // and O needs no rescale.  The final division by l_tot and the LSE absorb whatever reference was used.
+            const float mx2 = mx * c2;
+            const bool grow = mx2 > m_run + kLazy;        // first tile: m_run = -inf
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float m_new = grow ? mx2 : m_run;
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // first tile: exp2(-inf) = 0
+                m_run = m_new;
+                l_run *= alpha;
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int j = 0; j < 16; ++j) o_acc[db][j] *= alpha;
             }
+            float rs = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    s[mb][i] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[mb][i], c2, -m_run));
+                    rs += s[mb][i];
+                }
+            l_run += rs;
             // ---- O^T += V^T P^T : contraction over the 64 keys in 4 groups of 16
             const char *vst = stage + TILE_BYTES;
 #pragma unroll

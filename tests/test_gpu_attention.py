@@ -343,3 +343,16 @@ def test_fused_heads_dkv_accumulates_across_launches():
         assert np.abs(ref_c[:starts[0]]).max() > 0
     dkv2, _ = run_gpu()
     assert torch.equal(dkv, dkv2), "fused-heads dK/dV must be bitwise reproducible"
+
+
+def test_single_writer_flag_makes_dkv_bitwise_reproducible():
+    """CF_FLAG_DKV_SINGLE_WRITER: the dK/dV kernel's one-workgroup-per-key-tile mode on a small plan (long slices,
+    packed short sequences, GQA 8/2): matches the oracle, and two runs agree bit for bit in ALL five tensors."""
+    lens = [1500, 200, 77, 640, 129, 31]
+    a, _ = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=6, flags=B.CF_FLAG_DKV_SINGLE_WRITER)
+    b, _ = P.run_gpu(lens, 512, 8, 2, 128, "bf16", seed=6, flags=B.CF_FLAG_DKV_SINGLE_WRITER)
+    ref = P.run_oracle(lens, 8, 2, 128, "bf16", seed=6)
+    print(P.check(a, ref, "bf16", "single-writer dK/dV"))
+    for sid in a:
+        for n in P.NAMES:
+            assert np.array_equal(a[sid][n], b[sid][n]), (sid, n)
