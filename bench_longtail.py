@@ -10,7 +10,7 @@ device, building the descriptors) is outside the timed region, inputs are reside
 
 Prints one JSON line: total attention time, TFLOP/s over the unmasked pairs of the WHOLE batch, rounds.
 
-    python -m paper_2503_02356_amd.run_longtail_streamed [--tokens-per-round 1500000]
+    python bench_longtail.py [--tokens-per-round 1500000]
 """
 import argparse
 import json
@@ -18,7 +18,7 @@ import os
 import sys
 import time
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main():
@@ -36,7 +36,7 @@ def main():
     from paper_2503_02356_amd.runner import ChunkAttention
 
     if not torch.cuda.is_available():
-        sys.exit("run_longtail_streamed.py: no GPU visible")
+        sys.exit("bench_longtail.py: no GPU visible")
     cfg = inputs.CONFIGS["longtail_16k"]
     Hq, Hkv, D = cfg["Hq"], cfg["Hkv"], cfg["D"]
     lens, C = inputs.seq_lens("longtail_16k", args.seed, None)

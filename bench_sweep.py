@@ -9,7 +9,7 @@ Prints one JSON line per (ChunkSize, K): time of one Algorithm-2 step, TFLOP/s o
 (14 * D * Hq * unmasked pairs: re-forward passes cost time but add no useful FLOP), passes and re-forwards,
 and the bytes section 4.2's schedule keeps (kept chunk activations, key/value state).
 
-    python -m paper_2503_02356_amd.sweep_chunksize_k [--pairs 2048x16,8192x4,32768x1] [--steps 2]
+    python bench_sweep.py [--pairs 2048x16,8192x4,32768x1] [--steps 2]
 """
 import argparse
 import json
@@ -17,7 +17,7 @@ import os
 import sys
 import time
 
-sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 def main():

@@ -211,25 +211,28 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     const LaneOffsets lo = lane_offsets();
     char *exch = exch_all + pw * 2 * EXCH_SLOT_BYTES + lane * 16;   // this lane's 16 bytes of row group 0, slot 0
 
-    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles (issued by the role-1
-    // wavefronts); LSE and delta go through one register of 64 + 64 threads, loaded when the copy starts and turned
+    // Tile staging: Q and dO rows go straight from global memory into the swizzled LDS tiles (the first two tiles by the
+    // role-1 wavefronts, later ones shared: role 0 copies the Q tile, role 1 the dO tile, four copy instructions per
+    // wavefront and tile); LSE and delta go through one register of 64 + 64 threads, loaded when the copy starts and turned
     // into their LDS form (LSE as log2, +inf for rows past the segment so that P = 0; delta 0
     // there) one step later, so that nothing waits for memory right after the copies start.
     const int stid = tid - 256;                      // threads 256..319 / 320..383 (role 1) carry LSE / delta
     const float *stat_src = stid < 64 ? p.lse : delta;
-    TileDma<BQ, 4> dma_q, dma_do;                    // the four role-1 wavefronts copy (their VALU load is the lighter one)
+    TileDma<BQ, 4> dma_q, dma_do;                    // a tile is copied by the four wavefronts of one role
     dma_q.init(p.q_stride_tok * 2, pw);
     dma_do.init(b.do_stride_tok * 2, pw);
     int nx_h = h_first, nx_qt = qt_first;            // the tile the next copy fetches (advances by additions only)
     int stat_q0 = 0;                                 // first row of the tile the pending stat register belongs to
     float stat = 0.f;
-    auto issue_tile = [&](char *stage) {
+    auto issue_tile = [&](char *stage, bool with_q, bool with_do) {
         const int h = nx_h, q0 = nx_qt * BQ;
         const int64_t row0 = q_seg0 + q0;
-        dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
-        dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
-                     stage + QTILE_BYTES);
-        if (stid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
+        if (with_q)
+            dma_q.issue(uniform((const char *)p.q + (row0 * p.q_stride_tok + (int64_t)h * p.q_stride_head) * 2), lq - 1 - q0, stage);
+        if (with_do)
+            dma_do.issue(uniform((const char *)b.d_o + (row0 * b.do_stride_tok + (int64_t)h * b.do_stride_head) * 2), lq - 1 - q0,
+                         stage + QTILE_BYTES);
+        if (stid >= 0 && stid < 128) stat = stat_src[(int64_t)h * p.n_tokens + q_seg0 + min(q0 + (tid & 63), lq - 1)];
         stat_q0 = q0;
         if (++nx_qt == qt_end) {
             nx_qt = qt_first;
@@ -245,13 +248,16 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
     };
 
     if (role == 1) {
-        issue_tile(st0);
+        issue_tile(st0, true, true);
         publish_stats(st0);
         if (n_tiles > 1) {
-            issue_tile(st1);
+            issue_tile(st1, true, true);
             publish_stats(st1);
         }
         wait_lds_dma();
+    } else {                                         // role 0 shares the later copies: its tile counter moves along
+        issue_tile(st0, false, false);
+        if (n_tiles > 1) issue_tile(st1, false, false);
     }
     __syncthreads();
 
@@ -412,18 +418,22 @@ __device__ __forceinline__ void dkv_body(const cf_attn_bwd_params &b, const floa
         // s_cur1: stage of block k + 1
         auto step = [&](int k, const char *s_cur, const char *s_prev, char *s_next, const char *s_cur1) {
             const bool odd = k & 1;
-            if (ROLE == 1 && odd && (k + 3) / 2 < n_tiles) issue_tile(s_next);
+            if (odd && (k + 3) / 2 < n_tiles) issue_tile(s_next, ROLE == 0, ROLE == 1);
             if (ROLE == 0) {
                 if (k < n_blk) block_p_dv(k, s_cur, exch + (k & 1) * EXCH_SLOT_BYTES, s_cur1);
             } else {
                 if (k >= 1) finish_ds_dk(k - 1, s_prev, exch + ((k - 1) & 1) * EXCH_SLOT_BYTES, s_cur);
                 if (k < n_blk) start_dp(k, s_cur);
             }
-            if (ROLE == 1 && !odd) {                 // the copy started one step ago has had a full step to land
-                if (k >= 2 && (k + 2) / 2 < n_tiles) publish_stats(const_cast<char *>(s_cur == st0 ? st1 : s_cur == st1 ? st2 : st0));
+            if (!odd) {                              // the copy started one step ago has had a full step to land
+                if (ROLE == 1 && k >= 2 && (k + 2) / 2 < n_tiles) publish_stats(const_cast<char *>(s_cur == st0 ? st1 : s_cur == st1 ? st2 : st0));
                 wait_lds_dma();
             }
-            __syncthreads();
+            // The plain barrier instruction, not __syncthreads(): that one also orders memory, for which the compiler
+            // waits until a copy started in this very step has landed; the copies are waited for explicitly above, a
+            // step later.  lgkmcnt(0): this wavefront's own LDS writes (P, LSE, delta) are done.
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
         };
         // Six steps = three tiles per trip, so that every stage is a compile-time array in every position.
         for (int k = 0; k <= n_blk; k += 6) {
