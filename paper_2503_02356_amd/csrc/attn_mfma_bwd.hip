@@ -538,8 +538,14 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     const int G = p.n_q_heads / p.n_kv_heads;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
-    const int h = kh * G + id % G;
+    const int j = id % G;                            // which of the G workgroups of this (tile, key/value head)
     const int rank = id / G;
+    // Main blocks: the tile's 4 G units (32-row block, query head of the group) are dealt out four at a time,
+    // block-major (as in the forward kernel).  Head blocks: one query head, wavefront w takes block w.
+    const int unit = 4 * j + wave;
+    const int blk = HEAD_TILES ? wave : unit / G;
+    const int h = kh * G + (HEAD_TILES ? j : unit - blk * G);
+    const int blk_first = HEAD_TILES ? 0 : (4 * j) / G, blk_last = HEAD_TILES ? 3 : (4 * j + 3) / G;
 
     int tile_in_seg = 0, q_seg0, lq, k_seg0, lk;
     if (HEAD_TILES) {
@@ -563,9 +569,10 @@ __device__ __forceinline__ void dq_body(const cf_attn_bwd_params &b, float *__re
     // the tile whose rows sit among the first 128 positions of a sequence belongs to the head blocks
     if ((q_tile0 + off < 128) != HEAD_TILES) return;
     const int rows_valid = min(BM, lq - q_tile0);
-    const int kmax = q_tile0 + rows_valid + off;     // keys [0, kmax) are visible to some row of the tile
+    if (q_tile0 + blk_first * 32 >= lq) return;      // all four units lie beyond the last row
+    const int kmax = q_tile0 + min(rows_valid, (blk_last + 1) * 32) + off;   // keys [0, kmax) are visible to some row of the workgroup
     const int n_tiles = (kmax + BN - 1) / BN;
-    const int wq0 = q_tile0 + wave * 32;
+    const int wq0 = q_tile0 + blk * 32;
     const int wave_kmax = min(kmax, wq0 + 32 + off);
     const bool wave_active = wq0 < lq;
     const int iq = wq0 + col;                        // this lane's query row

@@ -36,8 +36,14 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
     const int G = p.n_q_heads / p.n_kv_heads;
     const int kh = id % p.n_kv_heads;
     id /= p.n_kv_heads;
-    const int h = kh * G + id % G;
+    const int j = id % G;                            // which of the G workgroups of this (tile, key/value head)
     const int rank = id / G;
+    // The tile's 4 G units (32-row block, query head of the group) are dealt out four at a time, block-major:
+    // the wavefronts of a workgroup then share at most two neighbouring blocks, so that they need (almost) the
+    // same key tiles and a ragged last tile costs workgroups in proportion to its rows.
+    const int unit = 4 * j + wave;
+    const int blk = unit / G;
+    const int h = kh * G + (unit - blk * G);
 
     int tile_in_seg, q_seg0, lq, k_seg0, lk;
     if (p.q_tiles != nullptr) {
@@ -54,10 +60,11 @@ __device__ __forceinline__ void fwd_body(const cf_attn_fwd_params &p, int id, ch
     const int off = lk - lq;                         // prefix keys every row of the segment sees
     const int q_tile0 = tile_in_seg * BM;
     const int rows_valid = min(BM, lq - q_tile0);
-    const int kmax = q_tile0 + rows_valid + off;     // keys [0, kmax) are visible to some row of the tile
+    if (q_tile0 + (4 * j) / G * 32 >= lq) return;    // all four units lie beyond the last row
+    const int kmax = q_tile0 + min(rows_valid, ((4 * j + 3) / G + 1) * 32) + off;   // keys [0, kmax) are visible to some row of the workgroup
     const int n_tiles = (kmax + BN - 1) / BN;
 
-    const int wq0 = q_tile0 + wave * 32;             // first row of this wavefront (segment-local)
+    const int wq0 = q_tile0 + blk * 32;              // first row of this wavefront (segment-local)
     const int wave_kmax = min(kmax, wq0 + 32 + off); // keys this wavefront needs (<= 0 rows valid: nothing)
     const bool wave_active = wq0 < lq;
     const int iq = wq0 + col;                        // this lane's query row
