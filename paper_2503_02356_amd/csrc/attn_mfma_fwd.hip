@@ -1,9 +1,11 @@
 // bf16 MFMA forward kernel for one chunk, head_dim 128 (paper sections 2.1, 2.2, 4.2: causal mask per
 // packed sequence; a dependent chunk's queries also read the retained key/value prefix).
 //
-// One workgroup = 4 wavefronts = 128 consecutive query rows of one segment and one query head; each
-// wavefront owns 32 rows.  Key/value tiles of 64 rows are copied straight from global memory into LDS
-// (buffer loads with an LDS destination, double buffered, XOR-swizzled rows) and shared by the four wavefronts.
+// One workgroup = 4 wavefronts; each wavefront owns a unit = 32 consecutive query rows of one query head.  A tile
+// of 128 rows and the G query heads of a key/value head make 4 G units, dealt four at a time (block-major) to G
+// workgroups: the units of a workgroup share the key/value head and (almost) the key range.  Key/value tiles
+// of 64 rows are copied straight from global memory into LDS (buffer loads with an LDS destination, double
+// buffered, XOR-swizzled rows) and shared by the four wavefronts.
 // Everything is computed TRANSPOSED so that a lane owns one query:
 //     S^T = K Q^T   (A = K tile rows from LDS, B = Q^T kept in registers for the whole kernel)
 //     O^T += V^T P^T (A = V^T through transposing LDS reads, B = P^T straight from the S^T registers)
