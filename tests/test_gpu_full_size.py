@@ -68,6 +68,7 @@ def run_full(cfg, seed, on_device=False, pick_groups=None):
     eng.run_forward()
     eng.run_backward()
     torch.cuda.synchronize()
+    print(f"{cfg}: {plan.n_chunks} chunks planned, forward + backward done on the GPU", flush=True)
     return lens, C, plan, eng, values
 
 
@@ -188,6 +189,7 @@ def check_tail_keys(eng, g, k0, v0, q_tail, do_tail, W, G, what):
     query rows of its G query heads."""
     L = k0.shape[0]
     qs, dos = np.ascontiguousarray(q_tail[:, :G]), np.ascontiguousarray(do_tail[:, :G])
+    print(f"{what}: oracle ...", flush=True)
     o, lse = OA.chunk_attn_fwd(qs, k0, v0, [0, W], [0, L], SCALE)
     dk, dv = np.zeros((L, 1, D)), np.zeros((L, 1, D))
     OA.chunk_attn_bwd(qs, k0, v0, o, lse, dos, [0, W], [0, L], SCALE, dk, dv)
@@ -213,6 +215,7 @@ def check_chunk_size_independence(eng, g, values, sid, L, C, what):
     """GPU vs GPU: the same sequence chunked at C and at C/2 (all rows, all heads, all five tensors).  Both are
     within the tolerance of the exact result, so they differ by at most twice that."""
     HQ, HKV = eng.Hq, eng.Hkv
+    print(f"{what}: second GPU run ...", flush=True)
     plan2, eng2 = rerun_with_chunk_size(values, sid, L, HQ, HKV, C // 2)
     assert plan2.n_chunks == -(-L // (C // 2))
     st, st2 = eng.state[g], eng2.state[0]
@@ -257,7 +260,9 @@ def test_config3_full_size_long_sequence_group_and_all_packed_sequences():
     t0 = time.time()
     sl = {"q": v["q"][:, :G], "d_o": v["d_o"][:, :G], "k": v["k"][:, :1], "v": v["v"][:, :1]}
     sl = {k: np.ascontiguousarray(x) for k, x in sl.items()}
+    print("GPU run done; oracle forward of the 32768-token sequence ...", flush=True)
     o, lse = OA.seq_attn_fwd(sl["q"], sl["k"], sl["v"], SCALE)
+    print(f"oracle forward: {time.time() - t0:.0f} s; backward ...", flush=True)
     dq, dk, dv = OA.seq_attn_bwd(sl["q"], sl["k"], sl["v"], o, lse, sl["d_o"], SCALE)
     print(f"oracle: 32768-token sequence, heads 0-{G - 1}: {time.time() - t0:.0f} s", flush=True)
     chunks = plan.group(g)
