@@ -8,18 +8,17 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    from tests import parity
+    parity.set_pytest_config(config)
 
 
 import pytest  # noqa: E402
 
 
 @pytest.fixture(autouse=True)
-def _gpu_tests_report_progress(request, capsys):
-    """GPU tests write their name before they touch the device, and their progress lines as they go (not only when
-    the test ends): a long oracle comparison is then visibly alive, and a crash names its case."""
-    if request.node.get_closest_marker("gpu") is None:
-        yield
-        return
-    with capsys.disabled():
-        print(f"\n[gpu test] {request.node.nodeid}", flush=True)
-        yield
+def _gpu_tests_name_themselves(request):
+    """A GPU test writes its name before it touches the device: a crash then names its case."""
+    if request.node.get_closest_marker("gpu") is not None:
+        from tests import parity
+        parity.progress(f"\n[gpu test] {request.node.nodeid}")
+    yield

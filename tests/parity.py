@@ -60,3 +60,22 @@ def run_oracle(lens, Hq, Hkv, D, dtype, seed, scale=None):
     seqs = {i: inputs.seq_values(seed, i, L, Hq, Hkv, D, dtype) for i, L in enumerate(lens)}
     s = scale if scale is not None else 1.0 / np.sqrt(D)
     return run_unsplit(seqs, np.float32(s))
+
+
+_PYTEST_CONFIG = None
+
+
+def set_pytest_config(config):
+    global _PYTEST_CONFIG
+    _PYTEST_CONFIG = config
+
+
+def progress(*args):
+    """A progress line that reaches the terminal while the test is still running (pytest's capture would hold it
+    back until the test ends): minutes-long oracle comparisons stay visibly alive."""
+    capman = _PYTEST_CONFIG.pluginmanager.getplugin("capturemanager") if _PYTEST_CONFIG is not None else None
+    if capman is None:
+        print(*args, flush=True)
+        return
+    with capman.global_and_fixture_disabled():
+        print(*args, flush=True)

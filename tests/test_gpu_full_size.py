@@ -68,7 +68,7 @@ def run_full(cfg, seed, on_device=False, pick_groups=None):
     eng.run_forward()
     eng.run_backward()
     torch.cuda.synchronize()
-    print(f"{cfg}: {plan.n_chunks} chunks planned, forward + backward done on the GPU", flush=True)
+    P.progress(f"{cfg}: {plan.n_chunks} chunks planned, forward + backward done on the GPU")
     return lens, C, plan, eng, values
 
 
@@ -94,7 +94,7 @@ class Errors:
     def check(self, what):
         for name, (mx, num, den, n) in self.acc.items():
             rel = np.sqrt(num / den) if den > 0 else 0.0
-            print(f"{what} {name}: {n} elements, max-abs {mx:.2e} rel-L2 {rel:.2e}", flush=True)
+            P.progress(f"{what} {name}: {n} elements, max-abs {mx:.2e} rel-L2 {rel:.2e}")
             assert np.isfinite(mx) and mx <= MAX_ABS and rel <= REL, (what, name, mx, rel)
 
 
@@ -123,7 +123,7 @@ def check_short_sequences(eng, values, picks, what):
             rel = np.sqrt(num / den) if den > 0 else 0.0
             assert mx <= MAX_ABS and rel <= REL, (what, "sequence", sid, "len", n, name, mx, rel)
         if (n_done + 1) % 20 == 0 or n_done + 1 == len(picks):
-            print(f"{what}: {n_done + 1}/{len(picks)} sequences checked, {time.time() - t0:.0f} s", flush=True)
+            P.progress(f"{what}: {n_done + 1}/{len(picks)} sequences checked, {time.time() - t0:.0f} s")
     errs.check(what)
 
 
@@ -180,7 +180,7 @@ def check_rows(eng, g, C, k_heads, v_heads, q_of, do_of, runs, what):
         errs.add("dq", f64(ch["d_q"][i:i + n, hs]), dq)
         n_rows += n
         if (m + 1) % 8 == 0 or m + 1 == len(runs):
-            print(f"{what}: {n_rows} rows in {m + 1}/{len(runs)} runs checked, {time.time() - t0:.0f} s", flush=True)
+            P.progress(f"{what}: {n_rows} rows in {m + 1}/{len(runs)} runs checked, {time.time() - t0:.0f} s")
     errs.check(what)
 
 
@@ -189,7 +189,7 @@ def check_tail_keys(eng, g, k0, v0, q_tail, do_tail, W, G, what):
     query rows of its G query heads."""
     L = k0.shape[0]
     qs, dos = np.ascontiguousarray(q_tail[:, :G]), np.ascontiguousarray(do_tail[:, :G])
-    print(f"{what}: oracle ...", flush=True)
+    P.progress(f"{what}: oracle ...")
     o, lse = OA.chunk_attn_fwd(qs, k0, v0, [0, W], [0, L], SCALE)
     dk, dv = np.zeros((L, 1, D)), np.zeros((L, 1, D))
     OA.chunk_attn_bwd(qs, k0, v0, o, lse, dos, [0, W], [0, L], SCALE, dk, dv)
@@ -215,7 +215,7 @@ def check_chunk_size_independence(eng, g, values, sid, L, C, what):
     """GPU vs GPU: the same sequence chunked at C and at C/2 (all rows, all heads, all five tensors).  Both are
     within the tolerance of the exact result, so they differ by at most twice that."""
     HQ, HKV = eng.Hq, eng.Hkv
-    print(f"{what}: second GPU run ...", flush=True)
+    P.progress(f"{what}: second GPU run ...")
     plan2, eng2 = rerun_with_chunk_size(values, sid, L, HQ, HKV, C // 2)
     assert plan2.n_chunks == -(-L // (C // 2))
     st, st2 = eng.state[g], eng2.state[0]
@@ -226,7 +226,7 @@ def check_chunk_size_independence(eng, g, values, sid, L, C, what):
     a_chunks, b_chunks = eng.plan.group(g), eng2.plan.group(0)
     for name, key, dim in (("o", "o", 0), ("dq", "d_q", 0), ("lse", "lse", 1)):
         out[name] = diff(cat(eng, a_chunks, key, dim), cat(eng2, b_chunks, key, dim))
-    print(what, {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in out.items()}, flush=True)
+    P.progress(what, {k: f"{v[0]:.2e}/{v[1]:.2e}" for k, v in out.items()})
     for name, (mx, rel) in out.items():
         assert mx <= 2 * MAX_ABS and rel <= 2 * REL, (what, name, mx, rel)
     del eng2
@@ -260,11 +260,19 @@ def test_config3_full_size_long_sequence_group_and_all_packed_sequences():
     t0 = time.time()
     sl = {"q": v["q"][:, :G], "d_o": v["d_o"][:, :G], "k": v["k"][:, :1], "v": v["v"][:, :1]}
     sl = {k: np.ascontiguousarray(x) for k, x in sl.items()}
-    print("GPU run done; oracle forward of the 32768-token sequence ...", flush=True)
-    o, lse = OA.seq_attn_fwd(sl["q"], sl["k"], sl["v"], SCALE)
-    print(f"oracle forward: {time.time() - t0:.0f} s; backward ...", flush=True)
-    dq, dk, dv = OA.seq_attn_bwd(sl["q"], sl["k"], sl["v"], o, lse, sl["d_o"], SCALE)
-    print(f"oracle: 32768-token sequence, heads 0-{G - 1}: {time.time() - t0:.0f} s", flush=True)
+    # (in two calls, heads 0-3 and 4-6: dK and dV of the key/value head are the sums over its query heads, and a
+    # progress line appears every minute or so)
+    o, lse, dq = np.empty_like(sl["q"]), np.empty((G, L)), np.empty_like(sl["q"])
+    dk, dv = np.zeros_like(sl["k"]), np.zeros_like(sl["k"])
+    for h0, h1 in ((0, 4), (4, G)):
+        qs, dos = np.ascontiguousarray(sl["q"][:, h0:h1]), np.ascontiguousarray(sl["d_o"][:, h0:h1])
+        o_p, lse_p = OA.seq_attn_fwd(qs, sl["k"], sl["v"], SCALE)
+        P.progress(f"oracle forward, heads {h0}-{h1 - 1}: {time.time() - t0:.0f} s; backward ...")
+        dq_p, dk_p, dv_p = OA.seq_attn_bwd(qs, sl["k"], sl["v"], o_p, lse_p, dos, SCALE)
+        o[:, h0:h1], lse[h0:h1], dq[:, h0:h1] = o_p, lse_p, dq_p
+        dk += dk_p
+        dv += dv_p
+        P.progress(f"oracle: 32768-token sequence, heads {h0}-{h1 - 1}: {time.time() - t0:.0f} s")
     chunks = plan.group(g)
     assert [eng.chunks[c]["P"] for c in chunks] == [0, 8192, 16384, 24576]
     errs = Errors()
@@ -321,7 +329,7 @@ def test_config4_full_size_sampled_groups():
         L = lens[sid]
         n_slices = -(-L // C)
         assert len(plan.group(picked[which])) == n_slices
-        print(f"{which} split sequence {sid}: {L} tokens, {n_slices} slices", flush=True)
+        P.progress(f"{which} split sequence {sid}: {L} tokens, {n_slices} slices")
         check_split_sequence(eng, values, sid, L, C, rng, f"config 4, {which} split sequence ({L} tokens)",
                              self_consistency=which == "longest")
     # whole short sequences of the two packed chunks (the oracle redoes each alone: keep them under 2000 tokens)
