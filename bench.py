@@ -178,7 +178,7 @@ def measure(workload, args, torch, np, B, inputs, ChunkAttention, extras=True):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="config2_packed_8k", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=0)
