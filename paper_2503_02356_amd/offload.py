@@ -68,8 +68,8 @@ class LayeredSequenceAttention:
             # the layer's state as the host holds it: key/value rows arrive when a chunk's forward has produced them
             h = {"k_state": torch.full((self.L, self.Hkv, self.D), float("nan"), dtype=dt).pin_memory(),
                  "v_state": torch.full((self.L, self.Hkv, self.D), float("nan"), dtype=dt).pin_memory(),
-                 "dk_state": torch.zeros((self.L, self.Hkv, self.D), dtype=torch.float32).pin_memory(),
-                 "dv_state": torch.zeros((self.L, self.Hkv, self.D), dtype=torch.float32).pin_memory()}
+                 "dk_state": torch.full((self.L, self.Hkv, self.D), float("nan"), dtype=torch.float32).pin_memory(),
+                 "dv_state": torch.full((self.L, self.Hkv, self.D), float("nan"), dtype=torch.float32).pin_memory()}
             self.host.append(h)
         self.slots = [_StateSlot(self.L, self.Hkv, self.D, dt, dev) for _ in range(self.window)]
         self.copy_in, self.copy_out = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
@@ -122,7 +122,9 @@ class LayeredSequenceAttention:
             rows = P + T if backward else P                    # backward: everything it reads; forward: the retained prefix
             self._copy(s.k[:rows], h["k_state"][:rows])
             self._copy(s.v[:rows], h["v_state"][:rows])
-            if backward:
+            # (the sequence's last chunk runs its backward first: no later chunk has added anything yet, so its
+            # gradient state does not travel in -- _compute clears it on the device)
+            if backward and m < len(self.chunks) - 1:
                 self._copy(s.dk[:rows], h["dk_state"][:rows])
                 self._copy(s.dv[:rows], h["dv_state"][:rows])
             s.loaded.record(self.copy_in)
@@ -136,6 +138,9 @@ class LayeredSequenceAttention:
         if not backward:                                       # this chunk's own keys/values enter the state
             s.k[P:P + T].copy_(a["k"][P:P + T])
             s.v[P:P + T].copy_(a["v"][P:P + T])
+        elif self.offload and m == len(self.chunks) - 1:       # first backward of the layer: gradients start at zero
+            s.dk[:P + T].zero_()                               # (fill kernels on the compute stream: the copy
+            s.dv[:P + T].zero_()                               # streams carry nothing but copies)
         fp = self._params(s, layer, m)
         handle = C.c_void_p(cur.cuda_stream)
         if backward:
@@ -166,9 +171,8 @@ class LayeredSequenceAttention:
     def run_step(self):
         """Forward over all chunks and layers, then backward; returns when everything is back on the host."""
         self.h2d_bytes = self.d2h_bytes = 0
-        for h in self.host:
-            h["dk_state"].zero_()
-            h["dv_state"].zero_()
+        # (offloaded: the host's gradient state needs no clearing -- the last chunk's backward, the first to run,
+        # writes all of its rows back)
         if not self.offload:
             for s in self.slots:
                 s.dk.zero_()
